@@ -1,0 +1,139 @@
+"""Benchmark of the AdaScale step on one MI355X.
+
+`python bench.py --gpus 1 --steps K --warmup W` times K whole adascale_step calls (all three
+kernels: reduce, scalars, update) on synthetic gradients already resident in HBM and prints ONE
+JSON line.  The workload is the configuration the headline metric is quoted on: d = 25,557,032
+parameters in 161 tensors (bottleneck-CNN-like shapes), S = 16 fp32 gradient buffers.
+
+value        = gradient bytes streamed per second (S*d*4 / step time), GB/s
+roofline     = the reduce kernel (dominant) against the 8 TB/s HBM peak: algorithmic bytes of one
+               launch (S*d*4 read + 4*d written) / its average duration, measured with HIP events
+               recorded by the library around each of its kernels inside the timed region
+cpu_baseline = the CPU oracle (OpenMP build of the same source) on the host, one step of the
+               same workload
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the headline configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not record per-kernel events inside the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as W
+    from paper_2007_05105_amd import AdaScale
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    wl = W.config(args.config)
+    inp = W.Inputs(wl, "cuda:0")
+    inp.fill_grads(0)
+    gpu = AdaScale(wl.numel, wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps,
+                   wl.grad_dtype, 0)
+    arr = lambda ts: (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+    pw, pv = arr(inp.w), arr(inp.v)
+    pg = arr([t for g in inp.g for t in g])
+    stream = torch.cuda.current_stream()
+    sh = int(stream.cuda_stream)
+
+    def run(n: int) -> None:
+        for _ in range(n):
+            rc = gpu.step_raw(pw, pv, pg, sh)
+            if rc != 0:
+                raise RuntimeError(gpu.last_error())
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    events = not args.no_kernel_events
+    if events:
+        gpu.profile_begin(args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, n_rec = (gpu.profile_end() if events else ((None, None, None), 0))
+    sec = (t1 - t0) / args.steps
+    st = gpu.get_state()
+
+    d, S, b = wl.d, wl.S, wl.grad_bytes
+    grad_bytes = S * d * b
+    total_bytes = grad_bytes + 24 * d
+    value = grad_bytes / sec / 1e9
+    reduce_bytes = grad_bytes + 4 * d
+    roof = None
+    if events and kernel_ms[0]:
+        ach = reduce_bytes / (kernel_ms[0] * 1e-3) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get(f"k_reduce_cfg{args.config}")
+        roof = {"bound": "hbm", "kernel": "k_reduce", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "bytes_per_launch": reduce_bytes, "avg_ms": round(kernel_ms[0], 5),
+                "other_kernels_ms": {"k_scalars": round(kernel_ms[1], 5), "k_update": round(kernel_ms[2], 5)},
+                "update_GBps": round(20 * d / (kernel_ms[2] * 1e-3) / 1e9, 1) if kernel_ms[2] else None}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import harness as H
+        orc = H.make_oracle(wl, openmp=True)
+        w64, v64 = H.params_to_numpy64(inp)
+        g_np = H.grads_to_numpy(inp)
+        reps, c0 = 0, time.perf_counter()
+        while reps < 1 or (time.perf_counter() - c0 < 10.0 and reps < 20):
+            orc.step(w64, v64, g_np)
+            reps += 1
+        csec = (time.perf_counter() - c0) / reps
+        cpu = {"value": round(grad_bytes / csec / 1e9, 3), "unit": "GB/s", "cores": orc.threads, "kind": "oracle",
+               "sample": f"{reps} full step(s) of the same workload ({S * d / 1e6:.0f}M gradient elements each), "
+                         f"OpenMP build of the oracle source, {csec:.3f} s/step"}
+
+    out = {
+        "metric": "adascale_step gradient GB/s (S*d*b / step time), 1 GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if b == 4 else "bf16->f32", "data": "synthetic",
+        "config": {"workload": wl.name, "d": d, "n_tensors": wl.n_tensors, "S": S, "grad_dtype": "fp32" if b == 4 else "bf16",
+                   "momentum": wl.momentum, "weight_decay": wl.weight_decay},
+        "total_GBps": round(total_bytes / sec / 1e9, 1),
+        "pct_hbm_peak": round(100 * total_bytes / sec / 1e9 / HBM_PEAK_GBPS, 2),
+        "grad_elements_per_s": round(S * d / sec, 0),
+        "algorithmic_bytes_per_step": total_bytes,
+        "final_state": {"step": st.step, "r": st.r, "tau": st.tau},
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    gpu.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

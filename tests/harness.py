@@ -1,0 +1,180 @@
+"""Shared by the GPU parity tests, the smoke check and the benchmark's CPU-baseline leg: feeds
+the same seeded inputs to the HIP library and to the CPU oracle and compares them.
+
+Two modes (both element by element on w and v):
+  teacher-forced : every checked step the oracle starts from the GPU's fp32 w, v and fp64
+                   scalar state of just before the step, so the comparison isolates the
+                   error of that one step (this is what the per-step tolerances grade);
+  free-running   : the oracle keeps its own state from step 0; the drift is reported.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Iterable, List, Optional
+
+import numpy as np
+import torch
+
+import workloads as W
+from oracle.oracle import Oracle
+from paper_2007_05105_amd import AdaScale
+
+# Tolerances of the benchmark definition: relative error on the scalars, elementwise error on
+# w (and v) relative to the largest magnitude in the same tensor.
+TOL_SCALAR = 1e-5
+TOL_W = 1e-6
+
+
+def grads_to_numpy(inp: W.Inputs) -> List[List[np.ndarray]]:
+    """The bit patterns of the S gradient buffers as numpy views per tensor (bf16 as uint16)."""
+    out = []
+    for i in range(inp.wl.S):
+        flat = inp.g_flat[i]
+        if flat.dtype == torch.bfloat16:
+            host = flat.view(torch.int16).cpu().numpy().view(np.uint16)
+        else:
+            host = flat.cpu().numpy()
+        out.append([host[o:o + n] for n, o in zip(inp.wl.numel, inp.offs_g)])
+    return out
+
+
+def params_to_numpy64(inp: W.Inputs):
+    wf = inp.w_flat.cpu().numpy().astype(np.float64)
+    vf = inp.v_flat.cpu().numpy().astype(np.float64)
+    w = [wf[o:o + n] for n, o in zip(inp.wl.numel, inp.offs32)]
+    v = [vf[o:o + n] for n, o in zip(inp.wl.numel, inp.offs32)]
+    return w, v
+
+
+def rel_err(got: float, ref: float, floor: float = 0.0) -> float:
+    den = max(abs(ref), floor)
+    return abs(got - ref) / den if den > 0 else abs(got - ref)
+
+
+@dataclass
+class StepReport:
+    step: int
+    rel: Dict[str, float]
+    w_err: float          # max over tensors of max|dw| / max|w| in that tensor
+    v_err: float
+    r: float
+    tau: float
+
+
+@dataclass
+class RunReport:
+    steps: List[StepReport] = field(default_factory=list)
+
+    def worst(self) -> Dict[str, float]:
+        out: Dict[str, float] = {}
+        for s in self.steps:
+            for k, x in list(s.rel.items()) + [("w", s.w_err), ("v", s.v_err)]:
+                out[k] = max(out.get(k, 0.0), x)
+        return out
+
+
+def make_gpu(wl: W.Workload, device: int = 0, flags: int = 0) -> AdaScale:
+    return AdaScale(wl.numel, wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps,
+                    wl.grad_dtype, device, flags)
+
+
+def make_oracle(wl: W.Workload, flags: int = 0, openmp: bool = False) -> Oracle:
+    return Oracle(wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps, wl.grad_dtype,
+                  flags, openmp)
+
+
+def compare_step(gpu_state, oracle_state, S: int) -> Dict[str, float]:
+    """Relative errors of the scalars.  sigma2_hat and mu2_hat cross zero in the noise- and
+    signal-dominated regimes, so they are measured against max(|value|, 1e-4 A/S), A/S being
+    their natural scale (sigma2 + mu2 = A/S)."""
+    floor = 1e-4 * oracle_state.sum_sq / S
+    return {
+        "sum_sq": rel_err(gpu_state.sum_sq, oracle_state.sum_sq),
+        "sq_mean": rel_err(gpu_state.sq_mean, oracle_state.sq_mean),
+        "sigma2_hat": rel_err(gpu_state.sigma2_hat, oracle_state.sigma2_hat, floor),
+        "mu2_hat": rel_err(gpu_state.mu2_hat, oracle_state.mu2_hat, floor),
+        "sigma2_bar": rel_err(gpu_state.sigma2_bar, oracle_state.sigma2_bar, floor),
+        "mu2_bar": rel_err(gpu_state.mu2_bar, oracle_state.mu2_bar, floor),
+        "r": rel_err(gpu_state.r, oracle_state.r),
+        "tau": rel_err(gpu_state.tau, oracle_state.tau),
+        "lr_eff": rel_err(gpu_state.lr_eff, oracle_state.lr_eff),
+    }
+
+
+def tensor_err(gpu_flat: torch.Tensor, ref: List[np.ndarray], before: List[np.ndarray], numel, offs) -> float:
+    """max over tensors of max|gpu - ref| / max(|ref|, |before|) within the tensor."""
+    host = gpu_flat.cpu().numpy().astype(np.float64)
+    worst = 0.0
+    for k, (n, o) in enumerate(zip(numel, offs)):
+        if n == 0:
+            continue
+        scale = max(np.abs(ref[k]).max(), np.abs(before[k]).max())
+        err = np.abs(host[o:o + n] - ref[k]).max()
+        if scale > 0:
+            worst = max(worst, err / scale)
+        elif err > 0:
+            worst = float("inf")
+    return worst
+
+
+def run_teacher_forced(wl: W.Workload, check_steps: Optional[Iterable[int]] = None, n_steps: Optional[int] = None,
+                       openmp: bool = False, flags: int = 0, skew_elems: int = 0, device: str = "cuda:0",
+                       inputs: Optional[W.Inputs] = None, log=None) -> RunReport:
+    n_steps = wl.steps if n_steps is None else n_steps
+    check = set(range(n_steps)) if check_steps is None else set(check_steps)
+    inp = inputs if inputs is not None else W.Inputs(wl, device, skew_elems=skew_elems)
+    gpu = make_gpu(wl, flags=flags)
+    orc = make_oracle(wl, flags=flags, openmp=openmp)
+    rep = RunReport()
+    for t in range(n_steps):
+        inp.fill_grads(t)
+        if t not in check:
+            gpu.step(inp.w, inp.v, inp.g)
+            continue
+        before = gpu.get_state()
+        w64, v64 = params_to_numpy64(inp)
+        w_before = [x.copy() for x in w64]
+        v_before = [x.copy() for x in v64]
+        gpu.step(inp.w, inp.v, inp.g)
+        after = gpu.get_state()
+        orc.set_state(before.step, before.tau, before.sigma2_bar, before.mu2_bar, before.r)
+        ost = orc.step(w64, v64, grads_to_numpy(inp))
+        sr = StepReport(t, compare_step(after, ost, wl.S),
+                        tensor_err(inp.w_flat, w64, w_before, wl.numel, inp.offs32),
+                        tensor_err(inp.v_flat, v64, v_before, wl.numel, inp.offs32), ost.r, ost.tau)
+        rep.steps.append(sr)
+        if log:
+            log(f"step {t}: r={ost.r:.6g} tau={ost.tau:.6g} worst_scalar={max(sr.rel.values()):.3g} "
+                f"w_err={sr.w_err:.3g} v_err={sr.v_err:.3g}")
+    gpu.close()
+    return rep
+
+
+def run_free(wl: W.Workload, n_steps: Optional[int] = None, openmp: bool = False, flags: int = 0,
+             device: str = "cuda:0"):
+    """Both sides run n_steps from the same start without exchanging state; returns the final
+    scalar comparison and the w drift."""
+    n_steps = wl.steps if n_steps is None else n_steps
+    inp = W.Inputs(wl, device)
+    gpu = make_gpu(wl, flags=flags)
+    orc = make_oracle(wl, flags=flags, openmp=openmp)
+    w64, v64 = params_to_numpy64(inp)
+    w0 = [x.copy() for x in w64]
+    ost = None
+    for t in range(n_steps):
+        inp.fill_grads(t)
+        gpu.step(inp.w, inp.v, inp.g)
+        ost = orc.step(w64, v64, grads_to_numpy(inp))
+    gst = gpu.get_state()
+    rel = compare_step(gst, ost, wl.S)
+    drift = tensor_err(inp.w_flat, w64, w0, wl.numel, inp.offs32)
+    gpu.close()
+    return rel, drift, gst, ost
+
+
+def assert_report(rep: RunReport, tol_scalar: float = TOL_SCALAR, tol_w: float = TOL_W) -> None:
+    for s in rep.steps:
+        for k in ("sigma2_hat", "mu2_hat", "r", "tau", "sigma2_bar", "mu2_bar", "lr_eff", "sum_sq", "sq_mean"):
+            assert s.rel[k] <= tol_scalar, f"step {s.step}: {k} rel err {s.rel[k]:.3g} > {tol_scalar}"
+        assert s.w_err <= tol_w, f"step {s.step}: |dw|/max|w| = {s.w_err:.3g} > {tol_w}"
+        assert s.v_err <= tol_w, f"step {s.step}: |dv|/max|v| = {s.v_err:.3g} > {tol_w}"
