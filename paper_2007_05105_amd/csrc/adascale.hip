@@ -13,8 +13,8 @@
 //
 // Work decomposition: every tensor is cut into tiles of 256 lanes x 16 bytes of gradient; the
 // tiles of all tensors form one list, cut into spans of `span_tiles` consecutive tiles.  A
-// workgroup handles whole spans and every wave writes its span partial to a slot fixed by
-// (span, wave), so the reduction result does not depend on scheduling.
+// workgroup handles whole spans and every workgroup writes its span partial to a slot fixed by
+// the span, so the reduction result does not depend on scheduling.
 
 #include <hip/hip_runtime.h>
 
@@ -31,7 +31,15 @@
 
 namespace {
 
-constexpr int kThreads = 256;
+// Gradient buffers are read exactly once per step: mark those loads non-temporal.
+#ifndef ADASCALE_NT_LOADS
+#define ADASCALE_NT_LOADS 1
+#endif
+#ifndef ADASCALE_THREADS
+#define ADASCALE_THREADS 256
+#endif
+
+constexpr int kThreads = ADASCALE_THREADS;
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kRing = 4;  // pinned staging slots for pointer-table uploads
@@ -76,12 +84,20 @@ __device__ __forceinline__ float widen(Bf16 x) { return __uint_as_float((unsigne
 // One 16-byte gradient load, unpacked to VEC floats.
 __device__ __forceinline__ void load_grad_vec(const float *p, float (&x)[4])
 {
+#if ADASCALE_NT_LOADS
     f4 t = __builtin_nontemporal_load((gp_cf4)(p));
+#else
+    f4 t = *(gp_cf4)(p);
+#endif
     x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
 }
 __device__ __forceinline__ void load_grad_vec(const Bf16 *p, float (&x)[8])
 {
+#if ADASCALE_NT_LOADS
     u4 t = __builtin_nontemporal_load((gp_cu4)(p));
+#else
+    u4 t = *(gp_cu4)(p);
+#endif
     const unsigned w[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -133,6 +149,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
     const int row_len = S + kRowG;
+    __shared__ double sh[kWaves][2];
 
     for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
         const int t0 = span * span_tiles;
@@ -205,10 +222,17 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
         acc_a = wave_sum(acc_a);
         acc_b = wave_sum(acc_b);
         if ((tid & (kWave - 1)) == 0) {
-            const size_t slot = ((size_t)span * kWaves + (tid >> 6)) * 2;
-            partials[slot] = acc_a;
-            partials[slot + 1] = acc_b;
+            sh[tid >> 6][0] = acc_a;
+            sh[tid >> 6][1] = acc_b;
         }
+        __syncthreads();
+        if (tid < 2) {  // fixed order over the waves
+            double t = sh[0][tid];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) t += sh[w][tid];
+            partials[(size_t)span * 2 + tid] = t;
+        }
+        __syncthreads();
     }
 }
 
@@ -228,21 +252,35 @@ __device__ __forceinline__ double gain_from(const ScalarArgs &c, double sbar, do
     return den > 0.0 ? (sbar + mbar) / den : 1.0;
 }
 
-__global__ __launch_bounds__(kThreads) void k_scalars(const double *__restrict__ partials, long long n_partials,
-                                                      DevState *__restrict__ st, const float *__restrict__ lr,
-                                                      ScalarArgs c)
+constexpr int kScalarThreads = 1024;
+
+__global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__restrict__ partials, int n_partials,
+                                                            DevState *__restrict__ st, const float *__restrict__ lr,
+                                                            ScalarArgs c)
 {
-    __shared__ double sh_a[kThreads], sh_b[kThreads];
+    __shared__ double sh_a[kScalarThreads], sh_b[kScalarThreads];
     const int tid = threadIdx.x;
+    typedef double d2 __attribute__((ext_vector_type(2)));
+    const d2 *p2 = reinterpret_cast<const d2 *>(partials);
     double a = 0.0, b = 0.0;
-    for (long long j = tid; j < n_partials; j += kThreads) {
-        a += partials[2 * j];
-        b += partials[2 * j + 1];
+    constexpr int U = 8;  // independent loads in flight per thread; the add order stays fixed
+    for (int j0 = tid; j0 < n_partials; j0 += kScalarThreads * U) {
+        d2 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + u * kScalarThreads;
+            x[u] = j < n_partials ? p2[j] : d2{0.0, 0.0};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a += x[u].x;
+            b += x[u].y;
+        }
     }
     sh_a[tid] = a;
     sh_b[tid] = b;
     __syncthreads();
-    for (int w = kThreads / 2; w > 0; w >>= 1) {
+    for (int w = kScalarThreads / 2; w > 0; w >>= 1) {
         if (tid < w) {
             sh_a[tid] += sh_a[tid + w];
             sh_b[tid] += sh_b[tid + w];
@@ -306,13 +344,16 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
                                                      const long long *__restrict__ numel,
                                                      const unsigned long long *__restrict__ ptrs,
                                                      const DevState *__restrict__ st, int n_tiles, int span_tiles,
-                                                     int n_spans, int row_len, float rho, float lambda)
+                                                     int n_spans, int row_len, float rho, float lambda,
+                                                     int reverse)
 {
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
     const float eta = st->eta_f32;
 
-    for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
+    for (int sp = blockIdx.x; sp < n_spans; sp += gridDim.x) {
+        // reverse: start with the spans whose mean gradient was written last
+        const int span = reverse ? n_spans - 1 - sp : sp;
         const int t0 = span * span_tiles;
         const int t1 = min(t0 + span_tiles, n_tiles);
         int k = span_first[span];
@@ -374,7 +415,8 @@ struct adascale_ctx {
     std::vector<size_t> gbar_off;   // element offset of tensor k in the mean-gradient scratch
     long long d = 0;
     int vec = 4, tile = 1024;
-    int n_tiles = 0, span_tiles = 4, n_spans = 0, max_blocks = 1 << 30, group = 0;
+    int n_tiles = 0, span_tiles = 2, n_spans = 0, max_blocks = 1 << 30, group = 0;
+    int update_reverse = 0;
     int S_cap = 0;                  // pointer table capacity in replicas
 
     int *d_span_first = nullptr, *d_tile_prefix = nullptr;
@@ -530,9 +572,10 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
     if (c->cfg.eps <= 0.0) c->cfg.eps = 1e-6;
     c->vec = cfg->grad_dtype == ADASCALE_F32 ? 4 : 8;
     c->tile = kThreads * c->vec;
-    c->span_tiles = env_int("ADASCALE_SPAN_TILES", 4);
+    c->span_tiles = env_int("ADASCALE_SPAN_TILES", 2);
     c->max_blocks = env_int("ADASCALE_MAX_BLOCKS", 1 << 30);
     c->group = env_int("ADASCALE_GROUP", 0);
+    c->update_reverse = env_int("ADASCALE_UPDATE_REVERSE", 0);
 
     const int N = cfg->n_tensors;
     c->numel.assign(cfg->numel, cfg->numel + N);
@@ -571,7 +614,7 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         HIP_TRY(c, hipMalloc(&c->d_numel, sizeof(long long) * std::max(N, 1)));
         HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * std::max<size_t>(goff, 64)));
         HIP_TRY(c, hipMalloc(&c->d_lr, sizeof(float) * cfg->lr_table_len));
-        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * kWaves * std::max(c->n_spans, 1)));
+        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * std::max(c->n_spans, 1)));
         HIP_TRY(c, hipMalloc(&c->d_state, sizeof(DevState)));
         HIP_TRY(c, hipHostMalloc(&c->h_state, sizeof(DevState), hipHostMallocDefault));
         for (int i = 0; i < kRing; ++i) HIP_TRY(c, hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
@@ -582,7 +625,7 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
             HIP_TRY(c, hipMemcpy(c->d_numel, c->numel.data(), sizeof(long long) * N, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_lr, cfg->lr_table, sizeof(float) * cfg->lr_table_len, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemset(c->d_state, 0, sizeof(DevState)));
-        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * kWaves * std::max(c->n_spans, 1)));
+        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * std::max(c->n_spans, 1)));
         return alloc_pointer_tables(c, cfg->S);
     };
     rc = body();
@@ -728,7 +771,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
     ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
-    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kThreads), 0, s, c->d_partials, (long long)c->n_spans * kWaves,
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans,
                        c->d_state, c->d_lr, sa);
     HIP_TRY(c, hipGetLastError());
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
@@ -737,11 +780,11 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         if (c->vec == 4)
             hipLaunchKernelGGL((k_update<4>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
                                c->d_numel, c->d_ptrs, c->d_state, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
-                               lambda);
+                               lambda, c->update_reverse);
         else
             hipLaunchKernelGGL((k_update<8>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
                                c->d_numel, c->d_ptrs, c->d_state, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
-                               lambda);
+                               lambda, c->update_reverse);
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));

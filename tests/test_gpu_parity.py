@@ -208,11 +208,13 @@ def test_config1_every_step_teacher_forced_and_free():
 
 @pytest.mark.timeout(600)
 def test_config2_full_run_sampled_steps():
-    """All 200 steps run on the GPU (r sweeps about 1.8 -> 7.9); the oracle checks a sample."""
+    """All 200 steps run on the GPU while the signal decays 1.0 -> 0.05 (the one-sample gain would
+    sweep about 1.8 -> 7.9; the theta = 0.992 average follows it with a lag); the oracle checks a
+    sample of the steps."""
     wl = W.config(2)
     rep = H.run_teacher_forced(wl, check_steps=[0, 1, 2, 49, 99, 149, 199], openmp=True, log=log)
     H.assert_report(rep)
-    assert rep.steps[0].r < 3.0 and rep.steps[-1].r > 6.0
+    assert rep.steps[0].r < 2.0 and rep.steps[-1].r > 3.5
 
 
 @pytest.mark.timeout(600)
