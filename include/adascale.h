@@ -143,11 +143,17 @@ const char *adascale_last_error(const adascale_ctx *ctx);
  * per-parameter traffic of the mean gradient, w and v.  For benchmarks; host only. */
 int64_t adascale_step_bytes(const adascale_ctx *ctx);
 
+/* 1 if this context runs the step as one fused cooperative launch that keeps the mean gradient
+ * on chip (fp32 gradients whose mean gradient mostly fits in registers + LDS), 0 if it runs the
+ * three-kernel step (reduce, scalars, update).  Both compute the same thing. */
+int adascale_uses_fused_step(const adascale_ctx *ctx);
+
 /*
  * Benchmark instrumentation: while profiling is on, every adascale_step also records HIP
  * events on its stream before and after each of its kernels (up to max_steps steps).
  * adascale_profile_end waits for the stream work, writes the average duration in
  * milliseconds of the reduce, scalars and update kernels over the recorded steps to ms[0..2]
+ * (a fused step reports its single kernel in ms[0])
  * and the number of recorded steps to *n_steps, and turns profiling off.
  */
 int adascale_profile_begin(adascale_ctx *ctx, int32_t max_steps);

@@ -18,7 +18,7 @@ _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
            "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_bytes",
-           "adascale_profile_begin", "adascale_profile_end"]
+           "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step"]
 
 
 class AdaScaleError(RuntimeError):
@@ -80,6 +80,8 @@ def load_library() -> C.CDLL:
         lib.adascale_profile_begin.restype = C.c_int
         lib.adascale_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         lib.adascale_profile_end.restype = C.c_int
+        lib.adascale_uses_fused_step.argtypes = [C.c_void_p]
+        lib.adascale_uses_fused_step.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -162,6 +164,9 @@ class AdaScale:
         n = C.c_int32()
         self._check(self._lib.adascale_profile_end(self._h, ms, C.byref(n)))
         return (ms[0], ms[1], ms[2]), n.value
+
+    def uses_fused_step(self) -> bool:
+        return bool(self._lib.adascale_uses_fused_step(self._h))
 
     def step_bytes(self) -> int:
         return int(self._lib.adascale_step_bytes(self._h))

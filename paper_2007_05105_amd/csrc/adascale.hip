@@ -252,11 +252,68 @@ __device__ __forceinline__ double gain_from(const ScalarArgs &c, double sbar, do
     return den > 0.0 ? (sbar + mbar) / den : 1.0;
 }
 
+// The estimator and the clock, evaluated by one lane.  Reads the state of before the step from
+// `in`, writes the state of after the step to `out` (two different records: other workgroups may
+// still be reading `in`).  Returns eta_t.
+__device__ __forceinline__ float eval_scalars(double A, double B, const DevState *__restrict__ in,
+                                              DevState *__restrict__ out, const float *__restrict__ lr,
+                                              const ScalarArgs &c, bool write)
+{
+    const int S = c.S;
+    double sig, mu;
+    if (S >= 2) {
+        sig = (A - S * B) / (S - 1);
+        mu = B - sig / S;
+    } else {
+        sig = 0.0;
+        mu = B;
+    }
+    double x1, x2;
+    if (c.flags & ADASCALE_EST_NORM_RATIO) {
+        x1 = A / S;
+        x2 = B;
+    } else {
+        x1 = S >= 2 ? fmax(sig, c.eps) : 0.0;
+        x2 = fmax(mu, 0.0);
+    }
+    const long long step = in->step;
+    const long long k = step + 1;
+    const double alpha = fmax(1.0 - c.theta, 1.0 / (double)k);
+    double sbar = in->sig_bar, mbar = in->mu_bar;
+    double r = 1.0;
+    if (c.flags & ADASCALE_LAGGED_R) r = step == 0 ? 1.0 : gain_from(c, sbar, mbar);
+    sbar += alpha * (x1 - sbar);
+    mbar += alpha * (x2 - mbar);
+    if (!(c.flags & ADASCALE_LAGGED_R)) r = gain_from(c, sbar, mbar);
+
+    const double tau = in->tau;
+    long long idx = (long long)floor(tau);
+    if (idx > c.L - 1) idx = c.L - 1;
+    if (idx < 0) idx = 0;
+    const double eta = r * (double)lr[idx];
+    if (write) {
+        out->A = A;
+        out->B = B;
+        out->sig_hat = sig;
+        out->mu_hat = mu;
+        out->sig_bar = sbar;
+        out->mu_bar = mbar;
+        out->r = r;
+        out->lr_eff = eta;
+        out->eta_f32 = (float)eta;
+        out->tau = tau + r;
+        out->step = k;
+        out->done = (tau + r) >= (double)c.L;
+    }
+    return (float)eta;
+}
+
 constexpr int kScalarThreads = 1024;
 
 __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__restrict__ partials, int n_partials,
-                                                            DevState *__restrict__ st, const float *__restrict__ lr,
-                                                            ScalarArgs c)
+                                                            const DevState *__restrict__ st_in,
+                                                            DevState *__restrict__ st_out,
+                                                            const float *__restrict__ lr, ScalarArgs c)
 {
     __shared__ double sh_a[kScalarThreads], sh_b[kScalarThreads];
     const int tid = threadIdx.x;
@@ -287,53 +344,7 @@ __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__rest
         }
         __syncthreads();
     }
-    if (tid != 0) return;
-
-    const double A = sh_a[0], B = sh_b[0];
-    const int S = c.S;
-    double sig, mu;
-    if (S >= 2) {
-        sig = (A - S * B) / (S - 1);
-        mu = B - sig / S;
-    } else {
-        sig = 0.0;
-        mu = B;
-    }
-    double x1, x2;
-    if (c.flags & ADASCALE_EST_NORM_RATIO) {
-        x1 = A / S;
-        x2 = B;
-    } else {
-        x1 = S >= 2 ? fmax(sig, c.eps) : 0.0;
-        x2 = fmax(mu, 0.0);
-    }
-    const long long k = st->step + 1;
-    const double alpha = fmax(1.0 - c.theta, 1.0 / (double)k);
-    double sbar = st->sig_bar, mbar = st->mu_bar;
-    double r = 1.0;
-    if (c.flags & ADASCALE_LAGGED_R) r = st->step == 0 ? 1.0 : gain_from(c, sbar, mbar);
-    sbar += alpha * (x1 - sbar);
-    mbar += alpha * (x2 - mbar);
-    if (!(c.flags & ADASCALE_LAGGED_R)) r = gain_from(c, sbar, mbar);
-
-    const double tau = st->tau;
-    long long idx = (long long)floor(tau);
-    if (idx > c.L - 1) idx = c.L - 1;
-    if (idx < 0) idx = 0;
-    const double eta = r * (double)lr[idx];
-
-    st->A = A;
-    st->B = B;
-    st->sig_hat = sig;
-    st->mu_hat = mu;
-    st->sig_bar = sbar;
-    st->mu_bar = mbar;
-    st->r = r;
-    st->lr_eff = eta;
-    st->eta_f32 = (float)eta;
-    st->tau = tau + r;
-    st->step = k;
-    st->done = (tau + r) >= (double)c.L;
+    if (tid == 0) eval_scalars(sh_a[0], sh_b[0], st_in, st_out, lr, c, true);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -391,6 +402,424 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fused step: one persistent cooperative launch, one workgroup per compute unit.
+//
+// Writing the mean gradient to HBM between the two passes is what the three-kernel step pays
+// most for: a small write stream mixed into the gradient reads lowers the read rate of the whole
+// pass, and the vector is read again by the update.  The chip can hold it instead: 256 CUs x
+// (160 KB LDS + 512 KB VGPR).  Phase 1 streams the S gradient buffers (reads only) and leaves
+// each lane's share of gbar in registers and LDS; a grid barrier makes A and B global; every
+// workgroup then sums the per-workgroup partials in the same fixed order, derives eta_t itself,
+// and phase 2 applies the momentum update from the retained values.
+//
+// Tiles here are 512 lanes x 4 elements.  Tiles that lie wholly inside a tensor ("full") take
+// the hot path: straight-line code without per-lane predicates.  Slot q of workgroup b is full
+// tile q * gridDim.x + b; slots [0, 30) live in VGPRs, the next lds_tiles slots in LDS, and any
+// further slots go through the HBM scratch like in the three-kernel step.  The ragged last tile
+// of each tensor ("cold", at most one per tensor) takes a simple predicated path through the
+// HBM scratch.
+constexpr int kFThreads = 512;                 // 8 waves: 2 per SIMD, up to 256 VGPRs each
+constexpr int kFWaves = kFThreads / kWave;
+constexpr int kFRegTiles = 30;                 // f4 per lane kept in VGPRs
+constexpr int kFTile = kFThreads * 4;          // elements per tile (fp32 gradients)
+constexpr int kFMaxGrid = 256;                 // workgroups (one per CU) = partial slots
+constexpr long long kFSpinLimit = 1LL << 22;   // bounded wait at the grid barrier
+
+struct FTile {
+    int k;      // tensor
+    int local;  // tile index inside the tensor
+};
+
+typedef const AS_GLOBAL char *gp_cchar;
+typedef AS_GLOBAL char *gp_char;
+// The tile, numel and pointer tables are never written while a kernel runs: reading them through
+// the constant address space lets the compiler use scalar loads even though the kernel stores to
+// other global memory (with plain global pointers it falls back to vector loads plus a full wait).
+#define AS_CONST __attribute__((address_space(4)))
+typedef const AS_CONST unsigned long long *cp_u64;
+
+// Where a full tile lives, in wave-uniform terms only (so it costs scalar registers): the
+// tensor's pointer row and the tile's byte offset inside the tensor (the same for w, v, the
+// scratch and every fp32 gradient buffer).  A lane adds its own constant byte offset 16 * tid.
+struct FLoc {
+    cp_u64 row;
+    unsigned long long tile_off;
+};
+
+// A tile's S = HG * NH replicas are consumed in NH (even) half-groups of HG replicas, alternating
+// between two register buffers: while one half-group is accumulated in fp64, the loads of the
+// next one (of the same tile, or of the next tile after the last half-group) are in flight.
+template <int HG>
+__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, f4 (&x)[HG])
+{
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+        x[g] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowG + first + g] + L.tile_off) + lane_off));
+}
+
+template <int HG>
+__device__ __forceinline__ void fused_accumulate(const f4 (&x)[HG], double (&s)[4], double &a)
+{
+#pragma unroll
+    for (int g = 0; g < HG; ++g) {
+        const float xv[4] = {x[g].x, x[g].y, x[g].z, x[g].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double xd = (double)xv[e];
+            s[e] += xd;
+            a = fma(xd, xd, a);
+        }
+        // keep the replicas in order: hoisting all fp32 -> fp64 conversions costs 2 VGPRs each
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Mean gradient of one full tile plus its contribution to A and B.  On entry `xa` holds (in
+// flight) half-group 0 of this tile; on return half-group 0 of the NEXT tile is in flight there
+// (the last tile of a workgroup names itself as next: 16 redundant loads, no branch).
+template <int HG, int NH>
+__device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, double inv_S,
+                                              f4 (&xa)[HG], double &acc_a, double &acc_b)
+{
+    static_assert(NH % 2 == 0, "half-groups alternate between two buffers");
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    double a = 0.0, b = 0.0;
+    f4 xb[HG];
+#pragma unroll
+    for (int h = 0; h < NH; h += 2) {
+        fused_issue<HG>(cur, lane_off, (h + 1) * HG, xb);
+        __builtin_amdgcn_sched_barrier(0);
+        fused_accumulate<HG>(xa, s, a);
+        __builtin_amdgcn_sched_barrier(0);
+        if (h + 2 < NH) fused_issue<HG>(cur, lane_off, (h + 2) * HG, xa);
+        else fused_issue<HG>(next, lane_off, 0, xa);
+        __builtin_amdgcn_sched_barrier(0);
+        fused_accumulate<HG>(xb, s, a);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const double m = s[e] * inv_S;
+        o[e] = (float)m;
+        b = fma(m, m, b);
+    }
+    acc_a += a;
+    acc_b += b;
+    // Keep the 8 waves of the workgroup on the same tile: left alone, the older waves win the
+    // arbitration for the memory pipeline and the workgroup then waits for its youngest wave.
+    __builtin_amdgcn_s_barrier();
+    return f4{o[0], o[1], o[2], o[3]};
+}
+
+__device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_off, f4 g, float eta, float rho,
+                                                  float lambda)
+{
+    gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
+    gp_char v = (gp_char)(L.row[kRowV] + L.tile_off) + lane_off;
+    const f4 wv = *(gp_cf4)w, vv = *(gp_cf4)v;
+    const float gv[4] = {g.x, g.y, g.z, g.w};
+    float wn[4] = {wv.x, wv.y, wv.z, wv.w}, vn[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float u = fmaf(lambda, wn[e], gv[e]);
+        vn[e] = fmaf(rho, vn[e], u);
+        wn[e] = fmaf(-eta, vn[e], wn[e]);
+    }
+    *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
+    *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
+}
+
+struct FusedArgs {
+    const FTile *tiles;            // full tiles   } read through the constant address space
+    const FTile *cold;             // ragged tiles }
+    const long long *numel;
+    const unsigned long long *ptrs;
+    double *partials;              // [gridDim.x][2]
+    const DevState *st_in;
+    DevState *st_out;
+    const float *lr;
+    unsigned long long *barrier;   // monotonically increasing arrival counter
+    unsigned long long barrier_target;
+    int *fault;                    // set when the bounded wait at the barrier gave up
+    int n_tiles, n_cold, tiles_per_block, lds_tiles, S;
+    double inv_S;
+    float rho, lambda;
+    ScalarArgs sc;
+#ifdef ADASCALE_FUSED_TIMING
+    unsigned long long *timing;    // [gridDim.x][8] wall-clock stamps (development builds only)
+#endif
+};
+
+#ifdef ADASCALE_FUSED_TIMING
+#define FUSED_STAMP(i)                                                  \
+    do {                                                                \
+        if (tid == 0) p.timing[(size_t)b * 8 + (i)] = wall_clock64();   \
+    } while (0)
+#else
+#define FUSED_STAMP(i) do { } while (0)
+#endif
+
+// Ragged last tile of a tensor, phase 1: per-lane predicates, mean gradient to the HBM scratch.
+// Lanes wholly inside the tensor use one 16-byte load per replica, the lane on the boundary
+// single elements; the replicas are loaded HG at a time so that their latencies overlap.
+template <int HG, int NH>
+__device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int tid, double &acc_a, double &acc_b)
+{
+    const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
+    const int k = tp[0], local = tp[1];
+    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * (p.S + kRowG);
+    const long long first = (long long)local * kFTile + (long long)tid * 4;
+    const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
+    if (rem <= 0) return;
+    const int c4 = rem < 4 ? (int)rem : 4;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    double a = 0.0, b = 0.0;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        f4 x[HG];
+#pragma unroll
+        for (int g = 0; g < HG; ++g) {
+            const AS_GLOBAL float *gp = (const AS_GLOBAL float *)row[kRowG + h * HG + g] + first;
+            if (c4 == 4) {
+                x[g] = __builtin_nontemporal_load((gp_cf4)gp);
+            } else {
+                x[g] = f4{gp[0], 0.f, 0.f, 0.f};
+                if (c4 > 1) x[g].y = gp[1];
+                if (c4 > 2) x[g].z = gp[2];
+            }
+        }
+        fused_accumulate<HG>(x, s, a);
+    }
+    AS_GLOBAL float *gb = (AS_GLOBAL float *)row[kRowGbar] + first;
+    float o[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const double m = s[e] * p.inv_S;   // elements past the end were loaded as zeros: m = 0
+        o[e] = (float)m;
+        b = fma(m, m, b);
+    }
+    if (c4 == 4) {
+        *(gp_f4)gb = f4{o[0], o[1], o[2], o[3]};
+    } else {
+        gb[0] = o[0];
+        if (c4 > 1) gb[1] = o[1];
+        if (c4 > 2) gb[2] = o[2];
+    }
+    acc_a += a;
+    acc_b += b;
+}
+
+__device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int tid, float eta)
+{
+    const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
+    const int k = tp[0], local = tp[1];
+    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * (p.S + kRowG);
+    const long long first = (long long)local * kFTile + (long long)tid * 4;
+    const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
+    if (rem <= 0) return;
+    AS_GLOBAL float *w = (AS_GLOBAL float *)row[kRowW] + first;
+    AS_GLOBAL float *v = (AS_GLOBAL float *)row[kRowV] + first;
+    const AS_GLOBAL float *gb = (const AS_GLOBAL float *)row[kRowGbar] + first;
+    if (rem >= 4) {
+        const f4 gv = *(gp_cf4)gb, wv = *(gp_cf4)w, vv = *(gp_cf4)v;
+        const float g4[4] = {gv.x, gv.y, gv.z, gv.w};
+        float wn[4] = {wv.x, wv.y, wv.z, wv.w}, vn[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float u = fmaf(p.lambda, wn[e], g4[e]);
+            vn[e] = fmaf(p.rho, vn[e], u);
+            wn[e] = fmaf(-eta, vn[e], wn[e]);
+        }
+        *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
+        *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
+    } else {
+#pragma unroll
+        for (int e = 0; e < 3; ++e) {
+            if (e < (int)rem) {
+                const float u = fmaf(p.lambda, w[e], gb[e]);
+                const float vn = fmaf(p.rho, v[e], u);
+                v[e] = vn;
+                w[e] = fmaf(-eta, vn, w[e]);
+            }
+        }
+    }
+}
+
+// The full-tile slots of one workgroup (wave-uniform).  Slot q holds full tile q * G + b; the
+// workgroup's slots [0, n_valid) exist.  Slots [0, 30) are kept in VGPRs, [30, q_hbm) in LDS,
+// [q_hbm, n_valid) go through the HBM scratch.
+struct FCtx {
+    const FusedArgs &p;
+    int b, G, row_len, q_hbm, n_valid;
+
+    __device__ __forceinline__ FLoc locate(int q) const
+    {
+        const AS_CONST int *tp = (const AS_CONST int *)p.tiles + 2 * ((size_t)q * G + b);
+        return FLoc{(cp_u64)p.ptrs + (size_t)tp[0] * row_len, (unsigned long long)tp[1] * (kFTile * 4ULL)};
+    }
+    // Phase 1 visits the HBM-spilled slots first (the only ones that write), then the LDS slots,
+    // then the register slots; after(q) is the slot visited after q, or q itself at the end.
+    __device__ __forceinline__ int after(int q) const
+    {
+        if (q >= q_hbm) return q + 1 < n_valid ? q + 1 : (kFRegTiles < q_hbm ? kFRegTiles : 0);
+        if (q >= kFRegTiles) return q + 1 < min(q_hbm, n_valid) ? q + 1 : 0;
+        return q + 1 < min(kFRegTiles, n_valid) ? q + 1 : q;
+    }
+};
+
+// Register slots, addressed at compile time (template recursion instead of a loop so that the
+// retained values are plain registers whatever the unroller decides).  Missing slots form a
+// suffix, so the recursion simply stops at the first one.
+template <int HG, int NH, int Q>
+__device__ __forceinline__ void fused_regs_phase1(const FCtx &cx, unsigned lane_off, f4 (&keep)[kFRegTiles], FLoc &cur,
+                                                  f4 (&xa)[HG], double &acc_a, double &acc_b)
+{
+    if constexpr (Q < kFRegTiles) {
+        if (Q < cx.n_valid) {
+            const FLoc next = cx.locate(cx.after(Q));
+            keep[Q] = fused_tile_mean<HG, NH>(cur, next, lane_off, cx.p.inv_S, xa, acc_a, acc_b);
+            cur = next;
+            fused_regs_phase1<HG, NH, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        }
+    }
+}
+
+template <int Q>
+__device__ __forceinline__ void fused_regs_phase2(const FCtx &cx, unsigned lane_off, const f4 (&keep)[kFRegTiles],
+                                                  float eta)
+{
+    if constexpr (Q < kFRegTiles) {
+        if (Q < cx.n_valid) {
+            fused_tile_update(cx.locate(Q), lane_off, keep[Q], eta, cx.p.rho, cx.p.lambda);
+            fused_regs_phase2<Q + 1>(cx, lane_off, keep, eta);
+        }
+    }
+}
+
+// S == HG * NH: (1,2) S = 2, (2,2) S = 4, (4,2) S = 8, (8,2) S = 16, (8,4) S = 32.
+template <int HG, int NH>
+__global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
+{
+    extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
+    __shared__ double red[kFMaxGrid][2];
+    __shared__ float sh_eta;
+    const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
+    // this workgroup's slots: full tiles b, b + G, b + 2G, ...
+    const int n_valid = b < p.n_tiles ? (p.n_tiles - 1 - b) / G + 1 : 0;
+    const int q_hbm = min(kFRegTiles + p.lds_tiles, p.tiles_per_block);
+    const int q_lds_end = min(q_hbm, n_valid);
+    const FCtx cx{p, b, G, p.S + kRowG, q_hbm, n_valid};
+    const unsigned lane_off = (unsigned)tid * 16u;
+
+    f4 keep[kFRegTiles];
+#pragma unroll
+    for (int q = 0; q < kFRegTiles; ++q) keep[q] = f4{0.f, 0.f, 0.f, 0.f};
+    double acc_a = 0.0, acc_b = 0.0;
+
+    // phase 1
+    FUSED_STAMP(0);
+    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<HG, NH>(p, c, tid, acc_a, acc_b);
+    FUSED_STAMP(1);
+
+    if (n_valid > 0) {
+        f4 xa[HG];
+        const int q_first = q_hbm < n_valid ? q_hbm : (kFRegTiles < n_valid ? kFRegTiles : 0);
+        FLoc cur = cx.locate(q_first);
+        fused_issue<HG>(cur, lane_off, 0, xa);
+        for (int q = q_hbm; q < n_valid; ++q) {
+            const FLoc next = cx.locate(cx.after(q));
+            const f4 m = fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
+            *(gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off) = m;
+            cur = next;
+        }
+        for (int q = kFRegTiles; q < q_lds_end; ++q) {
+            const FLoc next = cx.locate(cx.after(q));
+            lds_gbar[(q - kFRegTiles) * kFThreads + tid] =
+                fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
+            cur = next;
+        }
+        fused_regs_phase1<HG, NH, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+    }
+
+    // workgroup partial -> fixed slot
+    FUSED_STAMP(2);
+#ifdef ADASCALE_FUSED_TIMING
+    if (tid == kFThreads - 64) p.timing[(size_t)b * 8 + 7] = wall_clock64();
+#endif
+    acc_a = wave_sum(acc_a);
+    acc_b = wave_sum(acc_b);
+    if ((tid & (kWave - 1)) == 0) {
+        red[tid >> 6][0] = acc_a;
+        red[tid >> 6][1] = acc_b;
+    }
+    __syncthreads();
+    // The partials cross workgroups (and XCDs, whose L2s are not coherent with each other): they
+    // are written and read with agent-scope atomic accesses, which are performed at the memory
+    // side, and the arrival count is bumped only after this workgroup's stores have completed.
+    // That avoids a whole-L2 write-back and invalidate at the barrier; nothing else written in
+    // phase 1 (scratch tiles) is read by another workgroup.
+    if (tid < 2) {
+        double t = red[0][tid];
+#pragma unroll
+        for (int w = 1; w < kFWaves; ++w) t += red[w][tid];
+        __hip_atomic_store(&p.partials[(size_t)b * 2 + tid], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): the store has been acknowledged
+    }
+    FUSED_STAMP(5);
+
+    // grid barrier with a bounded wait
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_fetch_add(p.barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        long long spins = 0;
+        bool ok = true;
+        // poll not too often: 256 pollers share one address
+        while (__hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.barrier_target) {
+            __builtin_amdgcn_s_sleep(16);
+            if (++spins > kFSpinLimit) {
+                ok = false;
+                break;
+            }
+        }
+        if (!ok) __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    FUSED_STAMP(6);
+
+    // every workgroup: the same fixed-order sum of all partials, then the scalars
+    for (int j = tid; j < kFMaxGrid; j += kFThreads) {
+        red[j][0] = j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+        red[j][1] =
+            j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+    }
+    __syncthreads();
+    for (int w = kFMaxGrid / 2; w > 0; w >>= 1) {
+        for (int j = tid; j < w; j += kFThreads) {
+            red[j][0] += red[j + w][0];
+            red[j][1] += red[j + w][1];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], p.st_in, p.st_out, p.lr, p.sc, b == 0);
+    __syncthreads();
+    const float eta = sh_eta;
+    FUSED_STAMP(3);
+
+    // phase 2: momentum update from the retained mean gradient
+    fused_regs_phase2<0>(cx, lane_off, keep, eta);
+    for (int q = kFRegTiles; q < q_lds_end; ++q)
+        fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - kFRegTiles) * kFThreads + tid], eta, p.rho, p.lambda);
+    for (int q = q_hbm; q < n_valid; ++q) {
+        const FLoc L = cx.locate(q);
+        const f4 g = *(gp_cf4)((gp_cchar)(L.row[kRowGbar] + L.tile_off) + lane_off);
+        fused_tile_update(L, lane_off, g, eta, p.rho, p.lambda);
+    }
+    for (int c = b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);
+    FUSED_STAMP(4);
+}
+
 __global__ void k_set_state(DevState *st, long long step, double tau, double sbar, double mbar, long long L)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -424,7 +853,17 @@ struct adascale_ctx {
     unsigned long long *d_ptrs = nullptr;
     float *d_gbar = nullptr, *d_lr = nullptr;
     double *d_partials = nullptr;
-    DevState *d_state = nullptr;
+    DevState *d_state = nullptr;     // two records: [cur] is current, a step writes [cur ^ 1]
+    int cur = 0;
+    int *d_fault = nullptr;
+
+    // fused single-launch path
+    std::vector<FTile> ftiles, ctiles;   // full tiles, ragged last tiles
+    FTile *d_ftiles = nullptr, *d_ctiles = nullptr;
+    unsigned long long *d_barrier = nullptr;
+    unsigned long long fused_launches = 0;
+    int f_grid = 0, f_tpb = 0, f_lds_tiles = 0;
+    bool fused_ok = false;
 
     DevState *h_state = nullptr;    // pinned
     unsigned long long *h_ring[kRing] = {};
@@ -513,6 +952,67 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
     return a >= lo && a + bytes <= hi;
 }
 
+// The fused kernel instance that covers scale S (nullptr: none, use the three-kernel step).
+const void *fused_kernel_for(int S)
+{
+    switch (S) {
+    case 2: return reinterpret_cast<const void *>(k_fused<1, 2>);
+    case 4: return reinterpret_cast<const void *>(k_fused<2, 2>);
+    case 8: return reinterpret_cast<const void *>(k_fused<4, 2>);
+    case 16: return reinterpret_cast<const void *>(k_fused<8, 2>);
+    case 32: return reinterpret_cast<const void *>(k_fused<8, 4>);
+    default: return nullptr;
+    }
+}
+
+// Decide whether the fused single-launch step applies and build its tile tables.  It needs fp32
+// gradients, cooperative launch, and enough of the mean gradient to fit on chip to be worth it.
+int setup_fused(adascale_ctx *c)
+{
+    c->fused_ok = false;
+    if (env_int("ADASCALE_FUSED", 1) == 2) return ADASCALE_OK;              // 2 = force the three-kernel step
+    if (c->cfg.grad_dtype != ADASCALE_F32 || c->d == 0) return ADASCALE_OK;
+    hipDeviceProp_t prop;
+    HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
+    if (!prop.cooperativeLaunch) return ADASCALE_OK;
+    const int N = (int)c->numel.size();
+    c->ftiles.clear();
+    c->ctiles.clear();
+    for (int k = 0; k < N; ++k) {
+        if (c->numel[k] >= (1LL << 40)) return ADASCALE_OK;
+        const long long nf = c->numel[k] / kFTile;
+        if ((long long)c->ftiles.size() + nf > 0x3fffffffLL) return ADASCALE_OK;
+        for (long long j = 0; j < nf; ++j) c->ftiles.push_back(FTile{k, (int)j});
+        if (c->numel[k] % kFTile) c->ctiles.push_back(FTile{k, (int)nf});
+    }
+    const long long nt = (long long)c->ftiles.size(), nc = (long long)c->ctiles.size();
+    const int cus = std::min(std::min(prop.multiProcessorCount, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
+    const int grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
+    const int tpb = (int)((nt + grid - 1) / grid);
+    const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
+    const int lds_tiles = std::max(0, std::min(tpb - kFRegTiles, lds_cap));
+    const double on_chip = tpb == 0 ? 1.0 : std::min(1.0, (double)(kFRegTiles + lds_tiles) / tpb);
+    const double need = env_int("ADASCALE_FUSED_MIN_PCT", 50) / 100.0;
+    if (on_chip < need) return ADASCALE_OK;
+    const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
+    for (int S : {2, 4, 8, 16, 32}) {
+        const void *fn = fused_kernel_for(S);
+        HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+        int per_cu = 0;
+        HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
+        if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < grid) return ADASCALE_OK;
+    }
+    HIP_TRY(c, hipMalloc(&c->d_ftiles, sizeof(FTile) * std::max<size_t>(c->ftiles.size(), 1)));
+    HIP_TRY(c, hipMalloc(&c->d_ctiles, sizeof(FTile) * std::max<size_t>(c->ctiles.size(), 1)));
+    if (nt) HIP_TRY(c, hipMemcpy(c->d_ftiles, c->ftiles.data(), sizeof(FTile) * nt, hipMemcpyHostToDevice));
+    if (nc) HIP_TRY(c, hipMemcpy(c->d_ctiles, c->ctiles.data(), sizeof(FTile) * nc, hipMemcpyHostToDevice));
+    c->f_grid = grid;
+    c->f_tpb = tpb;
+    c->f_lds_tiles = lds_tiles;
+    c->fused_ok = true;
+    return ADASCALE_OK;
+}
+
 template <typename GT>
 void launch_reduce(const adascale_ctx *c, int grid, hipStream_t s, int S)
 {
@@ -544,6 +1044,8 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     const int64_t b = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
+
+int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S) ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -614,9 +1116,13 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         HIP_TRY(c, hipMalloc(&c->d_numel, sizeof(long long) * std::max(N, 1)));
         HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * std::max<size_t>(goff, 64)));
         HIP_TRY(c, hipMalloc(&c->d_lr, sizeof(float) * cfg->lr_table_len));
-        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * std::max(c->n_spans, 1)));
-        HIP_TRY(c, hipMalloc(&c->d_state, sizeof(DevState)));
-        HIP_TRY(c, hipHostMalloc(&c->h_state, sizeof(DevState), hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * std::max(c->n_spans, kFMaxGrid)));
+        HIP_TRY(c, hipMalloc(&c->d_state, 2 * sizeof(DevState)));
+        HIP_TRY(c, hipMalloc(&c->d_fault, sizeof(int)));
+        HIP_TRY(c, hipMalloc(&c->d_barrier, sizeof(unsigned long long)));
+        HIP_TRY(c, hipMemset(c->d_fault, 0, sizeof(int)));
+        HIP_TRY(c, hipMemset(c->d_barrier, 0, sizeof(unsigned long long)));
+        HIP_TRY(c, hipHostMalloc(&c->h_state, sizeof(DevState) + sizeof(int), hipHostMallocDefault));
         for (int i = 0; i < kRing; ++i) HIP_TRY(c, hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
         HIP_TRY(c, hipMemcpy(c->d_span_first, c->span_first.data(), sizeof(int) * c->span_first.size(),
                              hipMemcpyHostToDevice));
@@ -624,8 +1130,10 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         if (N > 0)
             HIP_TRY(c, hipMemcpy(c->d_numel, c->numel.data(), sizeof(long long) * N, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_lr, cfg->lr_table, sizeof(float) * cfg->lr_table_len, hipMemcpyHostToDevice));
-        HIP_TRY(c, hipMemset(c->d_state, 0, sizeof(DevState)));
-        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * std::max(c->n_spans, 1)));
+        HIP_TRY(c, hipMemset(c->d_state, 0, 2 * sizeof(DevState)));
+        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * std::max(c->n_spans, kFMaxGrid)));
+        const int frc = setup_fused(c);
+        if (frc != ADASCALE_OK) return frc;
         return alloc_pointer_tables(c, cfg->S);
     };
     rc = body();
@@ -651,6 +1159,10 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_lr);
     (void)hipFree(c->d_partials);
     (void)hipFree(c->d_state);
+    (void)hipFree(c->d_fault);
+    (void)hipFree(c->d_barrier);
+    (void)hipFree(c->d_ftiles);
+    (void)hipFree(c->d_ctiles);
     if (c->h_state) (void)hipHostFree(c->h_state);
     for (int i = 0; i < kRing; ++i) {
         if (c->h_ring[i]) (void)hipHostFree(c->h_ring[i]);
@@ -680,8 +1192,8 @@ int adascale_set_state(adascale_ctx *c, int64_t step, double tau, double sigma2_
     if (step < 0 || !(tau >= 0.0) || !(sigma2_bar >= 0.0) || !(mu2_bar >= 0.0))
         return fail(c, ADASCALE_EINVAL, "state values must be non-negative");
     HIP_TRY(c, hipSetDevice(c->cfg.device));
-    hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_state, (long long)step, tau,
-                       sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len);
+    hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_state + c->cur, (long long)step,
+                       tau, sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len);
     HIP_TRY(c, hipGetLastError());
     return ADASCALE_OK;
 }
@@ -692,8 +1204,11 @@ int adascale_get_state(adascale_ctx *c, adascale_state *out, void *hip_stream)
     if (!out) return fail(c, ADASCALE_EINVAL, "null out");
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(c, hipSetDevice(c->cfg.device));
-    HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state, sizeof(DevState), hipMemcpyDeviceToHost, s));
+    int *h_fault = reinterpret_cast<int *>(c->h_state + 1);
+    HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state + c->cur, sizeof(DevState), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipMemcpyAsync(h_fault, c->d_fault, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
+    if (*h_fault) return fail(c, ADASCALE_ESTATE, "a fused step gave up waiting at its grid barrier; results are invalid");
     const DevState &h = *c->h_state;
     out->step = h.step;
     out->tau = h.tau;
@@ -763,6 +1278,67 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     hipEvent_t *pe = nullptr;
     if (c->prof_on && c->prof_n < c->prof_cap) pe = &c->prof_ev[(size_t)4 * c->prof_n++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
+    ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
+    const DevState *st_in = c->d_state + c->cur;
+    DevState *st_out = c->d_state + (c->cur ^ 1);
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(S) : nullptr;
+    if (fused_fn) {
+        FusedArgs fa{};
+        fa.tiles = c->d_ftiles;
+        fa.cold = c->d_ctiles;
+        fa.n_cold = (int)c->ctiles.size();
+        fa.numel = c->d_numel;
+        fa.ptrs = c->d_ptrs;
+        fa.partials = c->d_partials;
+        fa.st_in = st_in;
+        fa.st_out = st_out;
+        fa.lr = c->d_lr;
+        fa.barrier = c->d_barrier;
+        fa.barrier_target = (c->fused_launches + 1) * (unsigned long long)c->f_grid;
+        fa.fault = c->d_fault;
+        fa.n_tiles = (int)c->ftiles.size();
+        fa.tiles_per_block = c->f_tpb;
+        fa.lds_tiles = c->f_lds_tiles;
+        fa.S = S;
+        fa.inv_S = 1.0 / (double)S;
+        fa.rho = (float)c->cfg.momentum;
+        fa.lambda = (float)c->cfg.weight_decay;
+        fa.sc = sa;
+#ifdef ADASCALE_FUSED_TIMING
+        static unsigned long long *d_timing = nullptr;
+        if (!d_timing) HIP_TRY(c, hipMalloc(&d_timing, sizeof(unsigned long long) * 8 * kFMaxGrid));
+        fa.timing = d_timing;
+        if (c->fused_launches == 60) {
+            std::vector<unsigned long long> h(8 * kFMaxGrid);
+            HIP_TRY(c, hipMemcpy(h.data(), d_timing, h.size() * 8, hipMemcpyDeviceToHost));
+            unsigned long long t0 = ~0ULL;
+            for (int i = 0; i < c->f_grid; ++i) t0 = std::min(t0, h[8 * i]);
+            for (int j = 0; j < 8; ++j) {
+                unsigned long long mn = ~0ULL, mx = 0;
+                double sum = 0;
+                for (int i = 0; i < c->f_grid; ++i) {
+                    const unsigned long long v = h[8 * i + j] - t0;
+                    mn = std::min(mn, v); mx = std::max(mx, v); sum += v;
+                }
+                fprintf(stderr, "stamp %d: min %.2f us  mean %.2f us  max %.2f us\n", j, mn / 100.0, sum / c->f_grid / 100.0, mx / 100.0);
+            }
+        }
+#endif
+        void *args[] = {&fa};
+#ifdef ADASCALE_FUSED_TIMING
+        if (getenv("ADASCALE_PLAIN_LAUNCH"))
+            HIP_TRY(c, hipLaunchKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args,
+                                       (size_t)c->f_lds_tiles * kFThreads * sizeof(f4), s));
+        else
+#endif
+        HIP_TRY(c, hipLaunchCooperativeKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args,
+                                              (size_t)c->f_lds_tiles * kFThreads * sizeof(f4), s));
+        c->fused_launches += 1;
+        c->cur ^= 1;
+        if (pe)
+            for (int j = 1; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
+        return ADASCALE_OK;
+    }
     const int grid = std::min(c->n_spans, c->max_blocks);
     if (grid > 0) {
         if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, grid, s, S);
@@ -770,20 +1346,20 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-    ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
-    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans,
-                       c->d_state, c->d_lr, sa);
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans, st_in, st_out,
+                       c->d_lr, sa);
     HIP_TRY(c, hipGetLastError());
+    c->cur ^= 1;
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
     if (grid > 0) {
         const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
         if (c->vec == 4)
             hipLaunchKernelGGL((k_update<4>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
-                               c->d_numel, c->d_ptrs, c->d_state, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
+                               c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
                                lambda, c->update_reverse);
         else
             hipLaunchKernelGGL((k_update<8>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
-                               c->d_numel, c->d_ptrs, c->d_state, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
+                               c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
                                lambda, c->update_reverse);
         HIP_TRY(c, hipGetLastError());
     }

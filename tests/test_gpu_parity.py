@@ -21,6 +21,19 @@ def log(msg):
     print(msg, flush=True)
 
 
+@pytest.fixture(autouse=True, params=["fused", "three_kernel"])
+def step_path(request, monkeypatch):
+    """Every test runs once per implementation of the step: the fused cooperative launch (fp32
+    gradients; the library picks it when enough of the mean gradient fits on chip) and the
+    three-kernel step (forced here; bf16 gradients always take it)."""
+    monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
+    return request.param
+
+
+def expect_path(gpu, step_path, dtype=F32):
+    assert gpu.uses_fused_step() == (step_path == "fused" and dtype == F32)
+
+
 # ------------------------------------------------------------------ small shapes, every path
 SMALL_SHAPES = [(5000,), (1,), (1023,), (1024,), (1025,), (3, 7, 11), (4096,), (64,), (2, 2049), (7,)]
 
@@ -33,6 +46,20 @@ def test_small_multi_tensor_all_scales(S, dtype):
                   lr_table=W.lr_step_decay(0.1, 8), steps=4, seed=S)
     rep = H.run_teacher_forced(wl, log=log)
     H.assert_report(rep)
+
+
+@pytest.mark.parametrize("S", [2, 4, 8, 16, 32])
+def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, step_path, monkeypatch):
+    """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
+    if step_path != "fused":
+        pytest.skip("fused step only")
+    monkeypatch.setenv("ADASCALE_FUSED_GRID", "2")
+    monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
+    wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, weight_decay=1e-3, theta=0.5, steps=3, seed=S)
+    g = H.make_gpu(wl)
+    assert g.uses_fused_step()
+    g.close()
+    H.assert_report(H.run_teacher_forced(wl, log=log))
 
 
 @pytest.mark.parametrize("skew", [1, 3])
@@ -60,6 +87,7 @@ def test_empty_tensors_and_empty_list():
     wl = W.custom([(0,), (300,), (0,), (0,), (5,)], 3, steps=2, seed=9)
     H.assert_report(H.run_teacher_forced(wl, log=log))
     g = AdaScale([], 4, [0.1], theta=0.0)
+    assert not g.uses_fused_step()
     g.step([], [], [[], [], [], []])
     st = g.get_state()
     assert st.step == 1 and st.sum_sq == 0.0 and st.sq_mean == 0.0 and st.r == 4.0 and st.tau == 4.0
@@ -196,8 +224,11 @@ def test_error_paths_launch_nothing():
 
 
 # ------------------------------------------------------------------------- the five configs
-def test_config1_every_step_teacher_forced_and_free():
+def test_config1_every_step_teacher_forced_and_free(step_path):
     wl = W.config(1)
+    g = H.make_gpu(wl)
+    expect_path(g, step_path)
+    g.close()
     rep = H.run_teacher_forced(wl, log=log)
     H.assert_report(rep)
     assert 3.5 < rep.steps[-1].r < 4.0
@@ -218,24 +249,31 @@ def test_config2_full_run_sampled_steps():
 
 
 @pytest.mark.timeout(600)
-def test_config3_benchmark_shape():
+def test_config3_benchmark_shape(step_path):
     """The configuration the benchmark times: d = 25.6M in 161 tensors, S = 16."""
     wl = W.config(3)
+    g = H.make_gpu(wl)
+    expect_path(g, step_path)
+    g.close()
     rep = H.run_teacher_forced(wl, n_steps=6, check_steps=[0, 1, 5], openmp=True, log=log)
     H.assert_report(rep)
 
 
 @pytest.mark.timeout(900)
-def test_config4_bf16():
+def test_config4_bf16(step_path):
+    if step_path == "fused":
+        pytest.skip("bf16 gradients always take the three-kernel step")
     wl = W.config(4)
     rep = H.run_teacher_forced(wl, n_steps=4, check_steps=[0, 3], openmp=True, log=log)
     H.assert_report(rep)
 
 
 @pytest.mark.timeout(1100)
-def test_config5_bf16_45GB():
+def test_config5_bf16_45GB(step_path):
     """d = 351M, S = 64: 45 GB of bf16 gradients resident; the oracle (OpenMP build) checks two
     steps of the signal-to-noise sweep, one noise dominated and one signal dominated."""
+    if step_path == "fused":
+        pytest.skip("bf16 gradients always take the three-kernel step")
     wl = W.config(5)
     inp = W.Inputs(wl, "cuda:0")
     rep = H.run_teacher_forced(wl, n_steps=2, check_steps=[0, 1], openmp=True, inputs=inp, log=log)
