@@ -39,6 +39,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel events inside the timed region")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB a few times (the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -53,6 +56,15 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 28                                   # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch copy_ kernel", "bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 5}))
+        return 0
     wl = W.config(args.config)
     inp = W.Inputs(wl, "cuda:0")
     inp.fill_grads(0)

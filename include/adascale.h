@@ -53,7 +53,16 @@ enum {
     ADASCALE_EST_NORM_RATIO = 2u,
     /* Skip the host-side check that every tensor pointer lies inside a device allocation
      * large enough for its tensor (done whenever the pointer set changes). */
-    ADASCALE_NO_POINTER_CHECK = 4u
+    ADASCALE_NO_POINTER_CHECK = 4u,
+    /* Launch the fused single-kernel step (see adascale_uses_fused_step) with
+     * hipLaunchCooperativeKernel.  Its grid barrier needs every workgroup resident at once; the
+     * grid is one workgroup per compute unit, so an ordinary launch (the default, about 15 us
+     * cheaper per step) satisfies that as soon as the compute units are free, and the library
+     * chains its own fused launches on a device so that two of them never hold half the chip
+     * each.  Set this flag if the process runs OTHER grid-synchronising kernels concurrently on
+     * the same device: the HIP runtime then serialises all of them.  In either mode the wait at
+     * the barrier is bounded; if it ever gives up, adascale_get_state returns ADASCALE_ESTATE. */
+    ADASCALE_COOPERATIVE_LAUNCH = 8u
 };
 
 typedef struct {

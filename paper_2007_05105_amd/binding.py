@@ -13,7 +13,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 F32, BF16 = 0, 1
-LAGGED_R, EST_NORM_RATIO, NO_POINTER_CHECK = 1, 2, 4
+LAGGED_R, EST_NORM_RATIO, NO_POINTER_CHECK, COOPERATIVE_LAUNCH = 1, 2, 4, 8
 _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",

@@ -24,6 +24,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -648,8 +649,10 @@ __device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int
 }
 
 // The full-tile slots of one workgroup (wave-uniform).  Slot q holds full tile q * G + b; the
-// workgroup's slots [0, n_valid) exist.  Slots [0, 30) are kept in VGPRs, [30, q_hbm) in LDS,
-// [q_hbm, n_valid) go through the HBM scratch.
+// workgroup's slots [0, n_valid) exist.  Slots [0, R) are kept in VGPRs (the host picks R so that
+// every workgroup has at least R tiles: that part is straight-line code without branches),
+// [R, q_hbm) in LDS, [q_hbm, n_valid) go through the HBM scratch.
+template <int R>
 struct FCtx {
     const FusedArgs &p;
     int b, G, row_len, q_hbm, n_valid;
@@ -663,43 +666,39 @@ struct FCtx {
     // then the register slots; after(q) is the slot visited after q, or q itself at the end.
     __device__ __forceinline__ int after(int q) const
     {
-        if (q >= q_hbm) return q + 1 < n_valid ? q + 1 : (kFRegTiles < q_hbm ? kFRegTiles : 0);
-        if (q >= kFRegTiles) return q + 1 < min(q_hbm, n_valid) ? q + 1 : 0;
-        return q + 1 < min(kFRegTiles, n_valid) ? q + 1 : q;
+        const int lds_end = min(q_hbm, n_valid);
+        if (q >= q_hbm) return q + 1 < n_valid ? q + 1 : (R < lds_end ? R : 0);
+        if (q >= R) return q + 1 < lds_end ? q + 1 : (R > 0 ? 0 : q);
+        return q + 1 < R ? q + 1 : q;
     }
 };
 
 // Register slots, addressed at compile time (template recursion instead of a loop so that the
-// retained values are plain registers whatever the unroller decides).  Missing slots form a
-// suffix, so the recursion simply stops at the first one.
-template <int HG, int NH, int Q>
-__device__ __forceinline__ void fused_regs_phase1(const FCtx &cx, unsigned lane_off, f4 (&keep)[kFRegTiles], FLoc &cur,
-                                                  f4 (&xa)[HG], double &acc_a, double &acc_b)
+// retained values are plain registers whatever the unroller decides).
+template <int HG, int NH, int R, int Q>
+__device__ __forceinline__ void fused_regs_phase1(const FCtx<R> &cx, unsigned lane_off, f4 (&keep)[R > 0 ? R : 1],
+                                                  FLoc &cur, f4 (&xa)[HG], double &acc_a, double &acc_b)
 {
-    if constexpr (Q < kFRegTiles) {
-        if (Q < cx.n_valid) {
-            const FLoc next = cx.locate(cx.after(Q));
-            keep[Q] = fused_tile_mean<HG, NH>(cur, next, lane_off, cx.p.inv_S, xa, acc_a, acc_b);
-            cur = next;
-            fused_regs_phase1<HG, NH, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
-        }
+    if constexpr (Q < R) {
+        const FLoc next = cx.locate(cx.after(Q));
+        keep[Q] = fused_tile_mean<HG, NH>(cur, next, lane_off, cx.p.inv_S, xa, acc_a, acc_b);
+        cur = next;
+        fused_regs_phase1<HG, NH, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 }
 
-template <int Q>
-__device__ __forceinline__ void fused_regs_phase2(const FCtx &cx, unsigned lane_off, const f4 (&keep)[kFRegTiles],
+template <int R, int Q>
+__device__ __forceinline__ void fused_regs_phase2(const FCtx<R> &cx, unsigned lane_off, const f4 (&keep)[R > 0 ? R : 1],
                                                   float eta)
 {
-    if constexpr (Q < kFRegTiles) {
-        if (Q < cx.n_valid) {
-            fused_tile_update(cx.locate(Q), lane_off, keep[Q], eta, cx.p.rho, cx.p.lambda);
-            fused_regs_phase2<Q + 1>(cx, lane_off, keep, eta);
-        }
+    if constexpr (Q < R) {
+        fused_tile_update(cx.locate(Q), lane_off, keep[Q], eta, cx.p.rho, cx.p.lambda);
+        fused_regs_phase2<R, Q + 1>(cx, lane_off, keep, eta);
     }
 }
 
-// S == HG * NH: (1,2) S = 2, (2,2) S = 4, (4,2) S = 8, (8,2) S = 16, (8,4) S = 32.
-template <int HG, int NH>
+// S == HG * NH; R = register slots per lane (every workgroup has at least R full tiles).
+template <int HG, int NH, int R>
 __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 {
     extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
@@ -708,14 +707,12 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
     // this workgroup's slots: full tiles b, b + G, b + 2G, ...
     const int n_valid = b < p.n_tiles ? (p.n_tiles - 1 - b) / G + 1 : 0;
-    const int q_hbm = min(kFRegTiles + p.lds_tiles, p.tiles_per_block);
+    const int q_hbm = min(R + p.lds_tiles, p.tiles_per_block);
     const int q_lds_end = min(q_hbm, n_valid);
-    const FCtx cx{p, b, G, p.S + kRowG, q_hbm, n_valid};
+    const FCtx<R> cx{p, b, G, p.S + kRowG, q_hbm, n_valid};
     const unsigned lane_off = (unsigned)tid * 16u;
 
-    f4 keep[kFRegTiles];
-#pragma unroll
-    for (int q = 0; q < kFRegTiles; ++q) keep[q] = f4{0.f, 0.f, 0.f, 0.f};
+    f4 keep[R > 0 ? R : 1];
     double acc_a = 0.0, acc_b = 0.0;
 
     // phase 1
@@ -725,7 +722,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 
     if (n_valid > 0) {
         f4 xa[HG];
-        const int q_first = q_hbm < n_valid ? q_hbm : (kFRegTiles < n_valid ? kFRegTiles : 0);
+        const int q_first = q_hbm < n_valid ? q_hbm : (R < q_lds_end ? R : 0);
         FLoc cur = cx.locate(q_first);
         fused_issue<HG>(cur, lane_off, 0, xa);
         for (int q = q_hbm; q < n_valid; ++q) {
@@ -734,13 +731,12 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
             *(gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off) = m;
             cur = next;
         }
-        for (int q = kFRegTiles; q < q_lds_end; ++q) {
+        for (int q = R; q < q_lds_end; ++q) {
             const FLoc next = cx.locate(cx.after(q));
-            lds_gbar[(q - kFRegTiles) * kFThreads + tid] =
-                fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
+            lds_gbar[(q - R) * kFThreads + tid] = fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
             cur = next;
         }
-        fused_regs_phase1<HG, NH, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        fused_regs_phase1<HG, NH, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 
     // workgroup partial -> fixed slot
@@ -808,9 +804,9 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     FUSED_STAMP(3);
 
     // phase 2: momentum update from the retained mean gradient
-    fused_regs_phase2<0>(cx, lane_off, keep, eta);
-    for (int q = kFRegTiles; q < q_lds_end; ++q)
-        fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - kFRegTiles) * kFThreads + tid], eta, p.rho, p.lambda);
+    if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
+    for (int q = R; q < q_lds_end; ++q)
+        fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
     for (int q = q_hbm; q < n_valid; ++q) {
         const FLoc L = cx.locate(q);
         const f4 g = *(gp_cf4)((gp_cchar)(L.row[kRowGbar] + L.tile_off) + lane_off);
@@ -832,6 +828,16 @@ __global__ void k_set_state(DevState *st, long long step, double tau, double sba
 }
 
 thread_local char g_init_error[256] = "";
+
+// Last fused launch on each device (see adascale_step).
+constexpr int kMaxDevices = 64;
+struct FusedChain {
+    std::mutex m;
+    hipEvent_t ev = nullptr;
+    hipStream_t last_stream = nullptr;
+    bool used = false;
+};
+FusedChain g_chain[kMaxDevices];
 
 }  // namespace
 
@@ -862,7 +868,7 @@ struct adascale_ctx {
     FTile *d_ftiles = nullptr, *d_ctiles = nullptr;
     unsigned long long *d_barrier = nullptr;
     unsigned long long fused_launches = 0;
-    int f_grid = 0, f_tpb = 0, f_lds_tiles = 0;
+    int f_grid = 0, f_tpb = 0, f_lds_tiles = 0, f_regs = 0;
     bool fused_ok = false;
 
     DevState *h_state = nullptr;    // pinned
@@ -952,15 +958,30 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
     return a >= lo && a + bytes <= hi;
 }
 
-// The fused kernel instance that covers scale S (nullptr: none, use the three-kernel step).
-const void *fused_kernel_for(int S)
+// Register-slot counts the fused kernel is instantiated for; the host uses the largest one that
+// every workgroup can fill.
+constexpr int kFRegChoices[] = {0, 10, 20, kFRegTiles};
+
+template <int R>
+const void *fused_kernel_for_r(int S)
 {
     switch (S) {
-    case 2: return reinterpret_cast<const void *>(k_fused<1, 2>);
-    case 4: return reinterpret_cast<const void *>(k_fused<2, 2>);
-    case 8: return reinterpret_cast<const void *>(k_fused<4, 2>);
-    case 16: return reinterpret_cast<const void *>(k_fused<8, 2>);
-    case 32: return reinterpret_cast<const void *>(k_fused<8, 4>);
+    case 2: return reinterpret_cast<const void *>(k_fused<1, 2, R>);
+    case 4: return reinterpret_cast<const void *>(k_fused<2, 2, R>);
+    case 8: return reinterpret_cast<const void *>(k_fused<4, 2, R>);
+    case 16: return reinterpret_cast<const void *>(k_fused<4, 4, R>);
+    default: return nullptr;
+    }
+}
+
+// The fused kernel instance for scale S and R register slots (nullptr: none, use the three-kernel step).
+const void *fused_kernel_for(int S, int R)
+{
+    switch (R) {
+    case 0: return fused_kernel_for_r<0>(S);
+    case 10: return fused_kernel_for_r<10>(S);
+    case 20: return fused_kernel_for_r<20>(S);
+    case kFRegTiles: return fused_kernel_for_r<kFRegTiles>(S);
     default: return nullptr;
     }
 }
@@ -974,7 +995,7 @@ int setup_fused(adascale_ctx *c)
     if (c->cfg.grad_dtype != ADASCALE_F32 || c->d == 0) return ADASCALE_OK;
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
-    if (!prop.cooperativeLaunch) return ADASCALE_OK;
+    if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
     const int N = (int)c->numel.size();
     c->ftiles.clear();
     c->ctiles.clear();
@@ -989,14 +1010,17 @@ int setup_fused(adascale_ctx *c)
     const int cus = std::min(std::min(prop.multiProcessorCount, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
     const int grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
     const int tpb = (int)((nt + grid - 1) / grid);
+    int regs = 0;  // register slots: the largest choice every workgroup can fill
+    for (int r : kFRegChoices)
+        if (r <= nt / grid) regs = r;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
-    const int lds_tiles = std::max(0, std::min(tpb - kFRegTiles, lds_cap));
-    const double on_chip = tpb == 0 ? 1.0 : std::min(1.0, (double)(kFRegTiles + lds_tiles) / tpb);
+    const int lds_tiles = std::max(0, std::min(tpb - regs, lds_cap));
+    const double on_chip = tpb == 0 ? 1.0 : std::min(1.0, (double)(regs + lds_tiles) / tpb);
     const double need = env_int("ADASCALE_FUSED_MIN_PCT", 50) / 100.0;
     if (on_chip < need) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
-    for (int S : {2, 4, 8, 16, 32}) {
-        const void *fn = fused_kernel_for(S);
+    for (int S : {2, 4, 8, 16}) {
+        const void *fn = fused_kernel_for(S, regs);
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
@@ -1009,6 +1033,7 @@ int setup_fused(adascale_ctx *c)
     c->f_grid = grid;
     c->f_tpb = tpb;
     c->f_lds_tiles = lds_tiles;
+    c->f_regs = regs;
     c->fused_ok = true;
     return ADASCALE_OK;
 }
@@ -1045,7 +1070,7 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
 
-int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S) ? 1 : 0; }
+int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S, c->f_regs) ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -1060,7 +1085,8 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
     if (!(cfg->weight_decay >= 0.0)) return fail(nullptr, ADASCALE_EINVAL, "negative weight decay");
     if (!(cfg->theta < 1.0)) return fail(nullptr, ADASCALE_EINVAL, "theta must be < 1");
     if (!cfg->lr_table || cfg->lr_table_len < 1) return fail(nullptr, ADASCALE_EINVAL, "empty lr table");
-    if (cfg->flags & ~(ADASCALE_LAGGED_R | ADASCALE_EST_NORM_RATIO | ADASCALE_NO_POINTER_CHECK))
+    if (cfg->flags & ~(ADASCALE_LAGGED_R | ADASCALE_EST_NORM_RATIO | ADASCALE_NO_POINTER_CHECK |
+                       ADASCALE_COOPERATIVE_LAUNCH))
         return fail(nullptr, ADASCALE_EINVAL, "unknown flag bits");
     for (int k = 0; k < cfg->n_tensors; ++k)
         if (cfg->numel[k] < 0) return fail(nullptr, ADASCALE_EINVAL, "negative numel");
@@ -1281,7 +1307,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
-    const void *fused_fn = c->fused_ok ? fused_kernel_for(S) : nullptr;
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(S, c->f_regs) : nullptr;
     if (fused_fn) {
         FusedArgs fa{};
         fa.tiles = c->d_ftiles;
@@ -1325,14 +1351,24 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         }
 #endif
         void *args[] = {&fa};
-#ifdef ADASCALE_FUSED_TIMING
-        if (getenv("ADASCALE_PLAIN_LAUNCH"))
-            HIP_TRY(c, hipLaunchKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args,
-                                       (size_t)c->f_lds_tiles * kFThreads * sizeof(f4), s));
-        else
-#endif
-        HIP_TRY(c, hipLaunchCooperativeKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args,
-                                              (size_t)c->f_lds_tiles * kFThreads * sizeof(f4), s));
+        const size_t lds_bytes = (size_t)c->f_lds_tiles * kFThreads * sizeof(f4);
+        if (c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) {
+            HIP_TRY(c, hipLaunchCooperativeKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args, lds_bytes, s));
+        } else {
+            // Ordinary launch (a cooperative one costs ~15 us more per step here).  The grid is one
+            // workgroup per CU, so all of it becomes resident as soon as the CUs are free; what
+            // must not happen is two fused kernels each holding part of the chip and waiting for
+            // the rest.  Fused launches of this process on one device are therefore chained: a
+            // launch on another stream than the previous one first waits for that one's event.
+            FusedChain &ch = g_chain[c->cfg.device % kMaxDevices];
+            std::lock_guard<std::mutex> lock(ch.m);
+            if (!ch.ev) HIP_TRY(c, hipEventCreateWithFlags(&ch.ev, hipEventDisableTiming));
+            if (ch.used && ch.last_stream != s) HIP_TRY(c, hipStreamWaitEvent(s, ch.ev, 0));
+            HIP_TRY(c, hipLaunchKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args, lds_bytes, s));
+            HIP_TRY(c, hipEventRecord(ch.ev, s));
+            ch.used = true;
+            ch.last_stream = s;
+        }
         c->fused_launches += 1;
         c->cur ^= 1;
         if (pe)
