@@ -117,7 +117,7 @@ def main() -> int:
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get(f"k_fused_cfg{args.config}")
-        roof = {"bound": "hbm", "kernel": "k_fused (whole step in one cooperative launch)", "achieved": round(ach, 1),
+        roof = {"bound": "hbm", "kernel": "k_fused (whole step in one launch)", "achieved": round(ach, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": total_bytes, "avg_ms": round(dev_ms, 5),
                 "timing": "HIP events on the launch stream around the K launches / K"}
