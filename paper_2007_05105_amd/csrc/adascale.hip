@@ -1,12 +1,14 @@
 // AdaScale SGD step for MI355X (gfx950): HIP kernels and the C ABI declared in adascale.h.
 //
-// One step is three launches on the caller's stream, none of which needs the host:
+// A step never needs the host.  In its general form it is three launches on the caller's stream:
 //   reduce  : one streaming pass over the S gradient buffers; writes the mean gradient
-//             (Sec. 2, Algorithm 1) and per-wave fp64 partial sums of A = sum_i ||g_i||^2
+//             (Sec. 2, Algorithm 1) and per-workgroup fp64 partial sums of A = sum_i ||g_i||^2
 //             and B = ||gbar||^2 (App. B.3);
 //   scalars : one workgroup sums the partials in a fixed order and evaluates the estimates,
 //             clamps, moving averages, gain ratio r_t, eta_t and tau (App. B.3, eq. 3, Sec. 3.2);
 //   update  : v <- rho v + gbar + lambda w, w <- w - eta_t v with eta_t read from device memory.
+// When the mean gradient fits on chip (fp32 gradients, see "fused step" below) the same work is
+// one persistent launch that keeps it in registers and LDS across a grid barrier.
 // The path is bandwidth bound (about half a flop per byte), so there is no matrix-core work:
 // the kernels are 16-byte-per-lane coalesced streams, 64-lane shuffle reductions and fp64
 // accumulation of exact squares.
@@ -82,31 +84,6 @@ struct Traits<Bf16> {
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(Bf16 x) { return __uint_as_float((unsigned)x.bits << 16); }
 
-// One 16-byte gradient load, unpacked to VEC floats.
-__device__ __forceinline__ void load_grad_vec(const float *p, float (&x)[4])
-{
-#if ADASCALE_NT_LOADS
-    f4 t = __builtin_nontemporal_load((gp_cf4)(p));
-#else
-    f4 t = *(gp_cf4)(p);
-#endif
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-__device__ __forceinline__ void load_grad_vec(const Bf16 *p, float (&x)[8])
-{
-#if ADASCALE_NT_LOADS
-    u4 t = __builtin_nontemporal_load((gp_cu4)(p));
-#else
-    u4 t = *(gp_cu4)(p);
-#endif
-    const unsigned w[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        x[2 * j] = __uint_as_float(w[j] << 16);
-        x[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
-    }
-}
-
 template <int VEC>
 __device__ __forceinline__ void load_f32(const float *p, float (&x)[VEC])
 {
@@ -137,17 +114,89 @@ __device__ __forceinline__ double wave_sum(double x)
 constexpr int kRowW = 0, kRowV = 1, kRowGbar = 2, kRowG = 3;
 
 // ---------------------------------------------------------------------------------------------
-// reduce: mean gradient + partial sums of A and B.  G = replicas loaded per batch of loads.
-template <typename GT, int G>
+// reduce: mean gradient + partial sums of A and B.  The S replicas of a tile are consumed in
+// half-groups of HG replicas that alternate between two register buffers, so that the loads of
+// the next half-group are in flight while the current one is accumulated.
+//
+// fp32 gradients are accumulated in fp64 (their squares are not exact in fp32).  bf16 gradients
+// are accumulated in fp32 and flushed to fp64 after every half-group: a product of two bf16
+// values is exact in fp32, and so is a sum of up to 64 bf16 values whose magnitudes lie within
+// 2^10 of each other; what rounding remains is random, below 2^-24 per operation, and averages
+// out over the ~1e5..1e9 flushed partials.
+__device__ __forceinline__ u4 load_raw(const void *p)
+{
+#if ADASCALE_NT_LOADS
+    return __builtin_nontemporal_load((gp_cu4)p);
+#else
+    return *(gp_cu4)p;
+#endif
+}
+
+struct AccF32 {  // for fp32 gradients
+    double s[4], a;
+    __device__ __forceinline__ void init() { s[0] = s[1] = s[2] = s[3] = 0.0; a = 0.0; }
+    __device__ __forceinline__ void add(u4 raw, bool live)
+    {
+        const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const double xd = live ? (double)__uint_as_float(w[e]) : 0.0;
+            s[e] += xd;
+            a = fma(xd, xd, a);
+        }
+    }
+    __device__ __forceinline__ void flush() {}
+    __device__ __forceinline__ double sum(int e) const { return s[e]; }
+    __device__ __forceinline__ double squares() const { return a; }
+};
+
+struct AccBf16 {  // for bf16 gradients
+    float s[8], af;
+    double a;
+    __device__ __forceinline__ void init()
+    {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] = 0.f;
+        af = 0.f;
+        a = 0.0;
+    }
+    __device__ __forceinline__ void add(u4 raw, bool live)
+    {
+        const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float lo = live ? __uint_as_float(w[j] << 16) : 0.f;
+            const float hi = live ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
+            s[2 * j] += lo;
+            s[2 * j + 1] += hi;
+            af = fmaf(lo, lo, af);
+            af = fmaf(hi, hi, af);
+        }
+    }
+    __device__ __forceinline__ void flush()
+    {
+        a += (double)af;
+        af = 0.f;
+    }
+    __device__ __forceinline__ double sum(int e) const { return (double)s[e]; }
+    __device__ __forceinline__ double squares() const { return a; }
+};
+
+template <typename GT> struct AccOf;
+template <> struct AccOf<float> { typedef AccF32 type; };
+template <> struct AccOf<Bf16> { typedef AccBf16 type; };
+
+template <typename GT, int HG>
 __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ span_first,
-                                                     const int *__restrict__ tile_prefix,
-                                                     const long long *__restrict__ numel,
-                                                     const unsigned long long *__restrict__ ptrs,
-                                                     double *__restrict__ partials, int n_tiles,
-                                                     int span_tiles, int n_spans, int S, double inv_S)
+                                                          const int *__restrict__ tile_prefix,
+                                                          const long long *__restrict__ numel,
+                                                          const unsigned long long *__restrict__ ptrs,
+                                                          double *__restrict__ partials, int n_tiles, int span_tiles,
+                                                          int n_spans, int S, double inv_S)
 {
     constexpr int VEC = Traits<GT>::VEC;
     constexpr int TILE = kThreads * VEC;
+    typedef typename AccOf<GT>::type Acc;
     const int tid = threadIdx.x;
     const int row_len = S + kRowG;
     __shared__ double sh[kWaves][2];
@@ -166,44 +215,44 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
             const unsigned long long *row = ptrs + (size_t)k * row_len;
             float *gbar = reinterpret_cast<float *>(row[kRowGbar]) + base;
 
-            double s[VEC];
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) s[e] = 0.0;
-            double a = 0.0;
-
             if (rem >= VEC) {
-                for (int i0 = 0; i0 < S; i0 += G) {
-                    float x[G][VEC];
+                Acc acc;
+                acc.init();
+                u4 xa[HG], xb[HG];
+                auto issue = [&](u4(&x)[HG], int first) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const int i = min(i0 + g, S - 1);  // past-the-end slots re-read the last replica
-                        load_grad_vec(reinterpret_cast<const GT *>(row[kRowG + i]) + base, x[g]);
+                    for (int g = 0; g < HG; ++g) {
+                        const int i = min(first + g, S - 1);  // past-the-end slots re-read the last replica
+                        x[g] = load_raw(reinterpret_cast<const GT *>(row[kRowG + i]) + base);
                     }
+                };
+                auto consume = [&](const u4(&x)[HG], int first) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const bool live = (i0 + g) < S;
-#pragma unroll
-                        for (int e = 0; e < VEC; ++e) {
-                            const double xd = live ? (double)x[g][e] : 0.0;
-                            s[e] += xd;
-                            a = fma(xd, xd, a);
-                        }
-                    }
+                    for (int g = 0; g < HG; ++g) acc.add(x[g], first + g < S);
+                    acc.flush();
+                };
+                issue(xa, 0);
+                for (int i0 = 0; i0 < S; i0 += 2 * HG) {
+                    const bool second = i0 + HG < S;
+                    if (second) issue(xb, i0 + HG);
+                    consume(xa, i0);
+                    if (i0 + 2 * HG < S) issue(xa, i0 + 2 * HG);
+                    if (second) consume(xb, i0 + HG);
                 }
                 float out[VEC];
                 double b = 0.0;
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
-                    const double m = s[e] * inv_S;
+                    const double m = acc.sum(e) * inv_S;
                     out[e] = (float)m;
                     b = fma(m, m, b);
                 }
                 store_f32<VEC>(gbar, out);
-                acc_a += a;
+                acc_a += acc.squares();
                 acc_b += b;
-            } else {  // ragged end of a tensor: element by element
+            } else {  // ragged end of a tensor: element by element, fp64
                 const int c = (int)rem;
-                double b = 0.0;
+                double a = 0.0, b = 0.0;
                 for (int e = 0; e < c; ++e) {
                     double se = 0.0;
                     for (int i = 0; i < S; ++i) {
@@ -228,10 +277,10 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
         }
         __syncthreads();
         if (tid < 2) {  // fixed order over the waves
-            double t = sh[0][tid];
+            double tsum = sh[0][tid];
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) t += sh[w][tid];
-            partials[(size_t)span * 2 + tid] = t;
+            for (int w = 1; w < kWaves; ++w) tsum += sh[w][tid];
+            partials[(size_t)span * 2 + tid] = tsum;
         }
         __syncthreads();
     }
@@ -1042,16 +1091,14 @@ template <typename GT>
 void launch_reduce(const adascale_ctx *c, int grid, hipStream_t s, int S)
 {
     const double inv_S = 1.0 / (double)S;
-    int G = c->group;
-    if (G <= 0) G = S >= 16 ? 16 : S >= 8 ? 8 : S >= 4 ? 4 : S >= 2 ? 2 : 1;
-#define LAUNCH(GG)                                                                                   \
-    hipLaunchKernelGGL((k_reduce<GT, GG>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,        \
+#define LAUNCH(HH)                                                                                   \
+    hipLaunchKernelGGL((k_reduce<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,        \
                        c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, c->n_tiles,           \
                        c->span_tiles, c->n_spans, S, inv_S)
-    if (G >= 16) LAUNCH(16);
-    else if (G >= 8) LAUNCH(8);
-    else if (G >= 4) LAUNCH(4);
-    else if (G >= 2) LAUNCH(2);
+    const int H = c->group > 0 ? c->group : 8;  // replicas per half-group (two half-groups in flight)
+    if (S >= 16 && H >= 8) LAUNCH(8);
+    else if (S >= 8 && H >= 4) LAUNCH(4);
+    else if (S >= 4 && H >= 2) LAUNCH(2);
     else LAUNCH(1);
 #undef LAUNCH
 }
