@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not record per-kernel events inside the timed region")
+    ap.add_argument("--lagged", action="store_true",
+                    help="time the prior-iteration-gain variant (App. B.3), a single sweep of S*d*b + 16*d bytes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB a few times (the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by) and exit")
@@ -69,7 +71,7 @@ def main() -> int:
     inp = W.Inputs(wl, "cuda:0")
     inp.fill_grads(0)
     gpu = AdaScale(wl.numel, wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps,
-                   wl.grad_dtype, 0)
+                   wl.grad_dtype, 0, flags=1 if args.lagged else 0)
     arr = lambda ts: (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
     pw, pv = arr(inp.w), arr(inp.v)
     pg = arr([t for g in inp.g for t in g])
@@ -159,7 +161,7 @@ def main() -> int:
         "pct_hbm_peak": round(100 * total_bytes / sec / 1e9 / HBM_PEAK_GBPS, 2),
         "grad_elements_per_s": round(S * d / sec, 0),
         "algorithmic_bytes_per_step": total_bytes,
-        "step_path": "fused" if fused else "three_kernel",
+        "step_path": ("fused" if fused else "three_kernel") + ("+lagged_gain" if args.lagged else ""),
         "final_state": {"step": st.step, "r": st.r, "tau": st.tau},
         "roofline": roof, "cpu_baseline": cpu,
     }

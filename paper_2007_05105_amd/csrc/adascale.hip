@@ -186,17 +186,96 @@ template <typename GT> struct AccOf;
 template <> struct AccOf<float> { typedef AccF32 type; };
 template <> struct AccOf<Bf16> { typedef AccBf16 type; };
 
+// Mean of the S replicas at one lane's VEC elements (all inside the tensor), and the lane's
+// contribution to A and B.
+template <typename GT, int HG>
+__device__ __forceinline__ void reduce_lane_full(const unsigned long long *__restrict__ row, long long base, int S,
+                                                 double inv_S, float (&out)[Traits<GT>::VEC], double &acc_a,
+                                                 double &acc_b)
+{
+    constexpr int VEC = Traits<GT>::VEC;
+    typename AccOf<GT>::type acc;
+    acc.init();
+    u4 xa[HG], xb[HG];
+    auto issue = [&](u4(&x)[HG], int first) {
+#pragma unroll
+        for (int g = 0; g < HG; ++g) {
+            const int i = min(first + g, S - 1);  // past-the-end slots re-read the last replica
+            x[g] = load_raw(reinterpret_cast<const GT *>(row[kRowG + i]) + base);
+        }
+    };
+    auto consume = [&](const u4(&x)[HG], int first) {
+#pragma unroll
+        for (int g = 0; g < HG; ++g) acc.add(x[g], first + g < S);
+        acc.flush();
+    };
+    issue(xa, 0);
+    for (int i0 = 0; i0 < S; i0 += 2 * HG) {
+        const bool second = i0 + HG < S;
+        if (second) issue(xb, i0 + HG);
+        consume(xa, i0);
+        if (i0 + 2 * HG < S) issue(xa, i0 + 2 * HG);
+        if (second) consume(xb, i0 + HG);
+    }
+    double b = 0.0;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const double m = acc.sum(e) * inv_S;
+        out[e] = (float)m;
+        b = fma(m, m, b);
+    }
+    acc_a += acc.squares();
+    acc_b += b;
+}
+
+// The same for one element at the ragged end of a tensor (fp64 throughout).
+template <typename GT>
+__device__ __forceinline__ float reduce_element(const unsigned long long *__restrict__ row, long long idx, int S,
+                                                double inv_S, double &acc_a, double &acc_b)
+{
+    double se = 0.0, a = 0.0;
+    for (int i = 0; i < S; ++i) {
+        const double xd = (double)widen(reinterpret_cast<const GT *>(row[kRowG + i])[idx]);
+        se += xd;
+        a = fma(xd, xd, a);
+    }
+    const double m = se * inv_S;
+    acc_a += a;
+    acc_b = fma(m, m, acc_b);
+    return (float)m;
+}
+
+// Workgroup sum of the lanes' (a, b) into the span's fixed partial slot.
+__device__ __forceinline__ void reduce_store_partial(double acc_a, double acc_b, double (&sh)[kWaves][2],
+                                                     double *__restrict__ partials, int span)
+{
+    const int tid = threadIdx.x;
+    acc_a = wave_sum(acc_a);
+    acc_b = wave_sum(acc_b);
+    if ((tid & (kWave - 1)) == 0) {
+        sh[tid >> 6][0] = acc_a;
+        sh[tid >> 6][1] = acc_b;
+    }
+    __syncthreads();
+    if (tid < 2) {  // fixed order over the waves
+        double tsum = sh[0][tid];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) tsum += sh[w][tid];
+        partials[(size_t)span * 2 + tid] = tsum;
+    }
+    __syncthreads();
+}
+
 template <typename GT, int HG>
 __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ span_first,
-                                                          const int *__restrict__ tile_prefix,
-                                                          const long long *__restrict__ numel,
-                                                          const unsigned long long *__restrict__ ptrs,
-                                                          double *__restrict__ partials, int n_tiles, int span_tiles,
-                                                          int n_spans, int S, double inv_S)
+                                                     const int *__restrict__ tile_prefix,
+                                                     const long long *__restrict__ numel,
+                                                     const unsigned long long *__restrict__ ptrs,
+                                                     double *__restrict__ partials, int n_tiles, int span_tiles,
+                                                     int n_spans, int S, double inv_S)
 {
     constexpr int VEC = Traits<GT>::VEC;
     constexpr int TILE = kThreads * VEC;
-    typedef typename AccOf<GT>::type Acc;
     const int tid = threadIdx.x;
     const int row_len = S + kRowG;
     __shared__ double sh[kWaves][2];
@@ -206,7 +285,6 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
         const int t1 = min(t0 + span_tiles, n_tiles);
         int k = span_first[span];
         double acc_a = 0.0, acc_b = 0.0;
-
         for (int t = t0; t < t1; ++t) {
             while (t >= tile_prefix[k + 1]) ++k;
             const long long base = (long long)(t - tile_prefix[k]) * TILE + (long long)tid * VEC;
@@ -214,75 +292,15 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
             if (rem <= 0) continue;
             const unsigned long long *row = ptrs + (size_t)k * row_len;
             float *gbar = reinterpret_cast<float *>(row[kRowGbar]) + base;
-
             if (rem >= VEC) {
-                Acc acc;
-                acc.init();
-                u4 xa[HG], xb[HG];
-                auto issue = [&](u4(&x)[HG], int first) {
-#pragma unroll
-                    for (int g = 0; g < HG; ++g) {
-                        const int i = min(first + g, S - 1);  // past-the-end slots re-read the last replica
-                        x[g] = load_raw(reinterpret_cast<const GT *>(row[kRowG + i]) + base);
-                    }
-                };
-                auto consume = [&](const u4(&x)[HG], int first) {
-#pragma unroll
-                    for (int g = 0; g < HG; ++g) acc.add(x[g], first + g < S);
-                    acc.flush();
-                };
-                issue(xa, 0);
-                for (int i0 = 0; i0 < S; i0 += 2 * HG) {
-                    const bool second = i0 + HG < S;
-                    if (second) issue(xb, i0 + HG);
-                    consume(xa, i0);
-                    if (i0 + 2 * HG < S) issue(xa, i0 + 2 * HG);
-                    if (second) consume(xb, i0 + HG);
-                }
                 float out[VEC];
-                double b = 0.0;
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    const double m = acc.sum(e) * inv_S;
-                    out[e] = (float)m;
-                    b = fma(m, m, b);
-                }
+                reduce_lane_full<GT, HG>(row, base, S, inv_S, out, acc_a, acc_b);
                 store_f32<VEC>(gbar, out);
-                acc_a += acc.squares();
-                acc_b += b;
-            } else {  // ragged end of a tensor: element by element, fp64
-                const int c = (int)rem;
-                double a = 0.0, b = 0.0;
-                for (int e = 0; e < c; ++e) {
-                    double se = 0.0;
-                    for (int i = 0; i < S; ++i) {
-                        const double xd = (double)widen(reinterpret_cast<const GT *>(row[kRowG + i])[base + e]);
-                        se += xd;
-                        a = fma(xd, xd, a);
-                    }
-                    const double m = se * inv_S;
-                    gbar[e] = (float)m;
-                    b = fma(m, m, b);
-                }
-                acc_a += a;
-                acc_b += b;
+            } else {
+                for (int e = 0; e < (int)rem; ++e) gbar[e] = reduce_element<GT>(row, base + e, S, inv_S, acc_a, acc_b);
             }
         }
-
-        acc_a = wave_sum(acc_a);
-        acc_b = wave_sum(acc_b);
-        if ((tid & (kWave - 1)) == 0) {
-            sh[tid >> 6][0] = acc_a;
-            sh[tid >> 6][1] = acc_b;
-        }
-        __syncthreads();
-        if (tid < 2) {  // fixed order over the waves
-            double tsum = sh[0][tid];
-#pragma unroll
-            for (int w = 1; w < kWaves; ++w) tsum += sh[w][tid];
-            partials[(size_t)span * 2 + tid] = tsum;
-        }
-        __syncthreads();
+        reduce_store_partial(acc_a, acc_b, sh, partials, span);
     }
 }
 
@@ -395,6 +413,79 @@ __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__rest
         __syncthreads();
     }
     if (tid == 0) eval_scalars(sh_a[0], sh_b[0], st_in, st_out, lr, c, true);
+}
+
+// eta_t of the prior-iteration variant (App. B.3): r_t from the averages as they stand before
+// the step (r_0 = 1), so it is known before any gradient is read.
+__device__ __forceinline__ float lagged_eta(const DevState *__restrict__ st, const float *__restrict__ lr,
+                                            const ScalarArgs &c)
+{
+    const double r = st->step == 0 ? 1.0 : gain_from(c, st->sig_bar, st->mu_bar);
+    long long idx = (long long)floor(st->tau);
+    if (idx > c.L - 1) idx = c.L - 1;
+    if (idx < 0) idx = 0;
+    return (float)(r * (double)lr[idx]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// single pass (prior-iteration gain): reduce and update in one sweep, S*d*b + 16*d bytes.  The
+// mean gradient never goes to memory; k_scalars afterwards folds A and B into the averages.
+template <typename GT, int HG>
+__global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restrict__ span_first,
+                                                            const int *__restrict__ tile_prefix,
+                                                            const long long *__restrict__ numel,
+                                                            const unsigned long long *__restrict__ ptrs,
+                                                            double *__restrict__ partials,
+                                                            const DevState *__restrict__ st,
+                                                            const float *__restrict__ lr, ScalarArgs sc, int n_tiles,
+                                                            int span_tiles, int n_spans, int S, double inv_S, float rho,
+                                                            float lambda)
+{
+    constexpr int VEC = Traits<GT>::VEC;
+    constexpr int TILE = kThreads * VEC;
+    const int tid = threadIdx.x;
+    const int row_len = S + kRowG;
+    __shared__ double sh[kWaves][2];
+    const float eta = lagged_eta(st, lr, sc);
+
+    for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
+        const int t0 = span * span_tiles;
+        const int t1 = min(t0 + span_tiles, n_tiles);
+        int k = span_first[span];
+        double acc_a = 0.0, acc_b = 0.0;
+        for (int t = t0; t < t1; ++t) {
+            while (t >= tile_prefix[k + 1]) ++k;
+            const long long base = (long long)(t - tile_prefix[k]) * TILE + (long long)tid * VEC;
+            const long long rem = numel[k] - base;
+            if (rem <= 0) continue;
+            const unsigned long long *row = ptrs + (size_t)k * row_len;
+            float *w = reinterpret_cast<float *>(row[kRowW]) + base;
+            float *v = reinterpret_cast<float *>(row[kRowV]) + base;
+            if (rem >= VEC) {
+                float wv[VEC], vv[VEC], gv[VEC];
+                load_f32<VEC>(w, wv);
+                load_f32<VEC>(v, vv);
+                reduce_lane_full<GT, HG>(row, base, S, inv_S, gv, acc_a, acc_b);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float u = fmaf(lambda, wv[e], gv[e]);
+                    vv[e] = fmaf(rho, vv[e], u);
+                    wv[e] = fmaf(-eta, vv[e], wv[e]);
+                }
+                store_f32<VEC>(v, vv);
+                store_f32<VEC>(w, wv);
+            } else {
+                for (int e = 0; e < (int)rem; ++e) {
+                    const float g = reduce_element<GT>(row, base + e, S, inv_S, acc_a, acc_b);
+                    const float u = fmaf(lambda, w[e], g);
+                    const float vn = fmaf(rho, v[e], u);
+                    v[e] = vn;
+                    w[e] = fmaf(-eta, vn, w[e]);
+                }
+            }
+        }
+        reduce_store_partial(acc_a, acc_b, sh, partials, span);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -747,7 +838,9 @@ __device__ __forceinline__ void fused_regs_phase2(const FCtx<R> &cx, unsigned la
 }
 
 // S == HG * NH; R = register slots per lane (every workgroup has at least R full tiles).
-template <int HG, int NH, int R>
+// LAG: prior-iteration gain (App. B.3) -- eta_t is known at the start, so there is no grid
+// barrier and no scalar evaluation here; k_scalars runs afterwards on the partials.
+template <int HG, int NH, int R, bool LAG>
 __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 {
     extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
@@ -800,58 +893,70 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         red[tid >> 6][1] = acc_b;
     }
     __syncthreads();
-    // The partials cross workgroups (and XCDs, whose L2s are not coherent with each other): they
-    // are written and read with agent-scope atomic accesses, which are performed at the memory
-    // side, and the arrival count is bumped only after this workgroup's stores have completed.
-    // That avoids a whole-L2 write-back and invalidate at the barrier; nothing else written in
-    // phase 1 (scratch tiles) is read by another workgroup.
-    if (tid < 2) {
-        double t = red[0][tid];
+    float eta;
+    if constexpr (LAG) {
+        if (tid < 2) {
+            double t = red[0][tid];
 #pragma unroll
-        for (int w = 1; w < kFWaves; ++w) t += red[w][tid];
-        __hip_atomic_store(&p.partials[(size_t)b * 2 + tid], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): the store has been acknowledged
-    }
-    FUSED_STAMP(5);
-
-    // grid barrier with a bounded wait
-    __syncthreads();
-    if (tid == 0) {
-        __hip_atomic_fetch_add(p.barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        long long spins = 0;
-        bool ok = true;
-        // poll not too often: 256 pollers share one address
-        while (__hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.barrier_target) {
-            __builtin_amdgcn_s_sleep(16);
-            if (++spins > kFSpinLimit) {
-                ok = false;
-                break;
-            }
+            for (int w = 1; w < kFWaves; ++w) t += red[w][tid];
+            p.partials[(size_t)b * 2 + tid] = t;
         }
-        if (!ok) __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __syncthreads();
-    FUSED_STAMP(6);
+        eta = lagged_eta(p.st_in, p.lr, p.sc);
+    } else {
+        // The partials cross workgroups (and XCDs, whose L2s are not coherent with each other): they
+        // are written and read with agent-scope atomic accesses, which are performed at the memory
+        // side, and the arrival count is bumped only after this workgroup's stores have completed.
+        // That avoids a whole-L2 write-back and invalidate at the barrier; nothing else written in
+        // phase 1 (scratch tiles) is read by another workgroup.
+        if (tid < 2) {
+            double t = red[0][tid];
+    #pragma unroll
+            for (int w = 1; w < kFWaves; ++w) t += red[w][tid];
+            __hip_atomic_store(&p.partials[(size_t)b * 2 + tid], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): the store has been acknowledged
+        }
+        FUSED_STAMP(5);
 
-    // every workgroup: the same fixed-order sum of all partials, then the scalars
-    for (int j = tid; j < kFMaxGrid; j += kFThreads) {
-        red[j][0] = j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-        red[j][1] =
-            j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-    }
-    __syncthreads();
-    for (int w = kFMaxGrid / 2; w > 0; w >>= 1) {
-        for (int j = tid; j < w; j += kFThreads) {
-            red[j][0] += red[j + w][0];
-            red[j][1] += red[j + w][1];
+        // grid barrier with a bounded wait
+        __syncthreads();
+        if (tid == 0) {
+            __hip_atomic_fetch_add(p.barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            long long spins = 0;
+            bool ok = true;
+            // poll not too often: 256 pollers share one address
+            while (__hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.barrier_target) {
+                __builtin_amdgcn_s_sleep(16);
+                if (++spins > kFSpinLimit) {
+                    ok = false;
+                    break;
+                }
+            }
+            if (!ok) __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         __syncthreads();
-    }
-    if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], p.st_in, p.st_out, p.lr, p.sc, b == 0);
-    __syncthreads();
-    const float eta = sh_eta;
-    FUSED_STAMP(3);
+        FUSED_STAMP(6);
 
+        // every workgroup: the same fixed-order sum of all partials, then the scalars
+        for (int j = tid; j < kFMaxGrid; j += kFThreads) {
+            red[j][0] = j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+            red[j][1] =
+                j < G ? __hip_atomic_load(&p.partials[(size_t)j * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+        }
+        __syncthreads();
+        for (int w = kFMaxGrid / 2; w > 0; w >>= 1) {
+            for (int j = tid; j < w; j += kFThreads) {
+                red[j][0] += red[j + w][0];
+                red[j][1] += red[j + w][1];
+            }
+            __syncthreads();
+        }
+        if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], p.st_in, p.st_out, p.lr, p.sc, b == 0);
+        __syncthreads();
+        eta = sh_eta;
+        FUSED_STAMP(3);
+
+
+    }
     // phase 2: momentum update from the retained mean gradient
     if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
     for (int q = R; q < q_lds_end; ++q)
@@ -1011,26 +1116,27 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
 // every workgroup can fill.
 constexpr int kFRegChoices[] = {0, 10, 20, kFRegTiles};
 
-template <int R>
+template <int R, bool LAG>
 const void *fused_kernel_for_r(int S)
 {
     switch (S) {
-    case 2: return reinterpret_cast<const void *>(k_fused<1, 2, R>);
-    case 4: return reinterpret_cast<const void *>(k_fused<2, 2, R>);
-    case 8: return reinterpret_cast<const void *>(k_fused<4, 2, R>);
-    case 16: return reinterpret_cast<const void *>(k_fused<4, 4, R>);
+    case 2: return reinterpret_cast<const void *>(k_fused<1, 2, R, LAG>);
+    case 4: return reinterpret_cast<const void *>(k_fused<2, 2, R, LAG>);
+    case 8: return reinterpret_cast<const void *>(k_fused<4, 2, R, LAG>);
+    case 16: return reinterpret_cast<const void *>(k_fused<4, 4, R, LAG>);
     default: return nullptr;
     }
 }
 
-// The fused kernel instance for scale S and R register slots (nullptr: none, use the three-kernel step).
-const void *fused_kernel_for(int S, int R)
+// The fused kernel instance for scale S, R register slots and gain variant (nullptr: none, use
+// the general step).
+const void *fused_kernel_for(int S, int R, bool lag)
 {
     switch (R) {
-    case 0: return fused_kernel_for_r<0>(S);
-    case 10: return fused_kernel_for_r<10>(S);
-    case 20: return fused_kernel_for_r<20>(S);
-    case kFRegTiles: return fused_kernel_for_r<kFRegTiles>(S);
+    case 0: return lag ? fused_kernel_for_r<0, true>(S) : fused_kernel_for_r<0, false>(S);
+    case 10: return lag ? fused_kernel_for_r<10, true>(S) : fused_kernel_for_r<10, false>(S);
+    case 20: return lag ? fused_kernel_for_r<20, true>(S) : fused_kernel_for_r<20, false>(S);
+    case kFRegTiles: return lag ? fused_kernel_for_r<kFRegTiles, true>(S) : fused_kernel_for_r<kFRegTiles, false>(S);
     default: return nullptr;
     }
 }
@@ -1069,7 +1175,7 @@ int setup_fused(adascale_ctx *c)
     if (on_chip < need) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
     for (int S : {2, 4, 8, 16}) {
-        const void *fn = fused_kernel_for(S, regs);
+        const void *fn = fused_kernel_for(S, regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
@@ -1103,6 +1209,23 @@ void launch_reduce(const adascale_ctx *c, int grid, hipStream_t s, int S)
 #undef LAUNCH
 }
 
+template <typename GT>
+void launch_reduce_update(const adascale_ctx *c, int grid, hipStream_t s, int S, const DevState *st, const ScalarArgs &sa)
+{
+    const double inv_S = 1.0 / (double)S;
+    const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
+#define LAUNCH(HH)                                                                                         \
+    hipLaunchKernelGGL((k_reduce_update<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,       \
+                       c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, st, c->d_lr, sa, c->n_tiles, \
+                       c->span_tiles, c->n_spans, S, inv_S, rho, lambda)
+    const int H = c->group > 0 ? c->group : 8;
+    if (S >= 16 && H >= 8) LAUNCH(8);
+    else if (S >= 8 && H >= 4) LAUNCH(4);
+    else if (S >= 4 && H >= 2) LAUNCH(2);
+    else LAUNCH(1);
+#undef LAUNCH
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -1117,7 +1240,7 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
 
-int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S, c->f_regs) ? 1 : 0; }
+int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S, c->f_regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -1354,7 +1477,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
-    const void *fused_fn = c->fused_ok ? fused_kernel_for(S, c->f_regs) : nullptr;
+    const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(S, c->f_regs, lag) : nullptr;
     if (fused_fn) {
         FusedArgs fa{};
         fa.tiles = c->d_ftiles;
@@ -1417,12 +1541,33 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             ch.last_stream = s;
         }
         c->fused_launches += 1;
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        if (lag) {
+            hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->f_grid, st_in, st_out,
+                               c->d_lr, sa);
+            HIP_TRY(c, hipGetLastError());
+        }
         c->cur ^= 1;
         if (pe)
-            for (int j = 1; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
+            for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
         return ADASCALE_OK;
     }
     const int grid = std::min(c->n_spans, c->max_blocks);
+    if (lag) {  // single pass (reduce + update with the prior-iteration gain), then the scalars
+        if (grid > 0) {
+            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, grid, s, S, st_in, sa);
+            else launch_reduce_update<Bf16>(c, grid, s, S, st_in, sa);
+            HIP_TRY(c, hipGetLastError());
+        }
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans, st_in, st_out,
+                           c->d_lr, sa);
+        HIP_TRY(c, hipGetLastError());
+        c->cur ^= 1;
+        if (pe)
+            for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
+        return ADASCALE_OK;
+    }
     if (grid > 0) {
         if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, grid, s, S);
         else launch_reduce<Bf16>(c, grid, s, S);

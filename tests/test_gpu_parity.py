@@ -114,6 +114,15 @@ def test_variants_of_the_estimator(flags):
     H.assert_report(H.run_teacher_forced(wl, flags=flags, log=log))
 
 
+@pytest.mark.parametrize("S,dtype", [(16, F32), (4, F32), (32, BF16), (5, F32)])
+def test_lagged_gain_single_pass_medium(S, dtype, step_path):
+    """Prior-iteration gain on shapes that span many tiles per workgroup: the step is one sweep
+    (reduce + update) followed by the scalar kernel."""
+    wl = W.custom([(3_000_000,), (70001,), (513,), (1_200_000,)], S, grad_dtype=dtype, weight_decay=1e-4, theta=0.9,
+                  lr_table=W.lr_step_decay(0.1, 64), steps=3, seed=41)
+    H.assert_report(H.run_teacher_forced(wl, flags=LAGGED_R, log=log))
+
+
 def test_cooperative_launch_flag(step_path):
     wl = W.custom([(300000,), (999,), (5000,)], 8, weight_decay=1e-3, theta=0.5, steps=3, seed=21)
     H.assert_report(H.run_teacher_forced(wl, flags=COOPERATIVE_LAUNCH, log=log))
