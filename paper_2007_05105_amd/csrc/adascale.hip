@@ -591,23 +591,28 @@ struct FLoc {
 // A tile's S = HG * NH replicas are consumed in NH (even) half-groups of HG replicas, alternating
 // between two register buffers: while one half-group is accumulated in fp64, the loads of the
 // next one (of the same tile, or of the next tile after the last half-group) are in flight.
-template <int HG>
-__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, f4 (&x)[HG])
-{
-#pragma unroll
-    for (int g = 0; g < HG; ++g)
-        x[g] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowG + first + g] + L.tile_off) + lane_off));
-}
-
-template <int HG>
-__device__ __forceinline__ void fused_accumulate(const f4 (&x)[HG], double (&s)[4], double &a)
+// MASK: S may be smaller than HG * NH; replica slots at or past S re-read the last replica (no
+// branch, the line is already on its way) and count as zero when accumulated.
+template <int HG, bool MASK>
+__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, int S, f4 (&x)[HG])
 {
 #pragma unroll
     for (int g = 0; g < HG; ++g) {
+        const int i = MASK ? min(first + g, S - 1) : first + g;
+        x[g] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowG + i] + L.tile_off) + lane_off));
+    }
+}
+
+template <int HG, bool MASK>
+__device__ __forceinline__ void fused_accumulate(const f4 (&x)[HG], int first, int S, double (&s)[4], double &a)
+{
+#pragma unroll
+    for (int g = 0; g < HG; ++g) {
+        const bool live = !MASK || first + g < S;
         const float xv[4] = {x[g].x, x[g].y, x[g].z, x[g].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const double xd = (double)xv[e];
+            const double xd = live ? (double)xv[e] : 0.0;
             s[e] += xd;
             a = fma(xd, xd, a);
         }
@@ -619,8 +624,8 @@ __device__ __forceinline__ void fused_accumulate(const f4 (&x)[HG], double (&s)[
 // Mean gradient of one full tile plus its contribution to A and B.  On entry `xa` holds (in
 // flight) half-group 0 of this tile; on return half-group 0 of the NEXT tile is in flight there
 // (the last tile of a workgroup names itself as next: 16 redundant loads, no branch).
-template <int HG, int NH>
-__device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, double inv_S,
+template <int HG, int NH, bool MASK>
+__device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, int S, double inv_S,
                                               f4 (&xa)[HG], double &acc_a, double &acc_b)
 {
     static_assert(NH % 2 == 0, "half-groups alternate between two buffers");
@@ -629,14 +634,14 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     f4 xb[HG];
 #pragma unroll
     for (int h = 0; h < NH; h += 2) {
-        fused_issue<HG>(cur, lane_off, (h + 1) * HG, xb);
+        fused_issue<HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
-        fused_accumulate<HG>(xa, s, a);
+        fused_accumulate<HG, MASK>(xa, h * HG, S, s, a);
         __builtin_amdgcn_sched_barrier(0);
-        if (h + 2 < NH) fused_issue<HG>(cur, lane_off, (h + 2) * HG, xa);
-        else fused_issue<HG>(next, lane_off, 0, xa);
+        if (h + 2 < NH) fused_issue<HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
+        else fused_issue<HG, MASK>(next, lane_off, 0, S, xa);
         __builtin_amdgcn_sched_barrier(0);
-        fused_accumulate<HG>(xb, s, a);
+        fused_accumulate<HG, MASK>(xb, (h + 1) * HG, S, s, a);
         __builtin_amdgcn_sched_barrier(0);
     }
     float o[4];
@@ -717,12 +722,11 @@ __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int t
     const int c4 = rem < 4 ? (int)rem : 4;
     double s[4] = {0.0, 0.0, 0.0, 0.0};
     double a = 0.0, b = 0.0;
-#pragma unroll
-    for (int h = 0; h < NH; ++h) {
+    for (int i0 = 0; i0 < p.S; i0 += HG) {
         f4 x[HG];
 #pragma unroll
         for (int g = 0; g < HG; ++g) {
-            const AS_GLOBAL float *gp = (const AS_GLOBAL float *)row[kRowG + h * HG + g] + first;
+            const AS_GLOBAL float *gp = (const AS_GLOBAL float *)row[kRowG + min(i0 + g, p.S - 1)] + first;
             if (c4 == 4) {
                 x[g] = __builtin_nontemporal_load((gp_cf4)gp);
             } else {
@@ -731,7 +735,7 @@ __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int t
                 if (c4 > 2) x[g].z = gp[2];
             }
         }
-        fused_accumulate<HG>(x, s, a);
+        fused_accumulate<HG, true>(x, i0, p.S, s, a);
     }
     AS_GLOBAL float *gb = (AS_GLOBAL float *)row[kRowGbar] + first;
     float o[4];
@@ -815,15 +819,15 @@ struct FCtx {
 
 // Register slots, addressed at compile time (template recursion instead of a loop so that the
 // retained values are plain registers whatever the unroller decides).
-template <int HG, int NH, int R, int Q>
+template <int HG, int NH, bool MASK, int R, int Q>
 __device__ __forceinline__ void fused_regs_phase1(const FCtx<R> &cx, unsigned lane_off, f4 (&keep)[R > 0 ? R : 1],
                                                   FLoc &cur, f4 (&xa)[HG], double &acc_a, double &acc_b)
 {
     if constexpr (Q < R) {
         const FLoc next = cx.locate(cx.after(Q));
-        keep[Q] = fused_tile_mean<HG, NH>(cur, next, lane_off, cx.p.inv_S, xa, acc_a, acc_b);
+        keep[Q] = fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, cx.p.S, cx.p.inv_S, xa, acc_a, acc_b);
         cur = next;
-        fused_regs_phase1<HG, NH, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        fused_regs_phase1<HG, NH, MASK, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 }
 
@@ -837,10 +841,10 @@ __device__ __forceinline__ void fused_regs_phase2(const FCtx<R> &cx, unsigned la
     }
 }
 
-// S == HG * NH; R = register slots per lane (every workgroup has at least R full tiles).
+// S == HG * NH (MASK: S <= HG * NH); R = register slots per lane (every workgroup has at least R full tiles).
 // LAG: prior-iteration gain (App. B.3) -- eta_t is known at the start, so there is no grid
 // barrier and no scalar evaluation here; k_scalars runs afterwards on the partials.
-template <int HG, int NH, int R, bool LAG>
+template <int HG, int NH, bool MASK, int R, bool LAG>
 __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 {
     extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
@@ -866,19 +870,20 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         f4 xa[HG];
         const int q_first = q_hbm < n_valid ? q_hbm : (R < q_lds_end ? R : 0);
         FLoc cur = cx.locate(q_first);
-        fused_issue<HG>(cur, lane_off, 0, xa);
+        fused_issue<HG, MASK>(cur, lane_off, 0, p.S, xa);
         for (int q = q_hbm; q < n_valid; ++q) {
             const FLoc next = cx.locate(cx.after(q));
-            const f4 m = fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
+            const f4 m = fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
             *(gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off) = m;
             cur = next;
         }
         for (int q = R; q < q_lds_end; ++q) {
             const FLoc next = cx.locate(cx.after(q));
-            lds_gbar[(q - R) * kFThreads + tid] = fused_tile_mean<HG, NH>(cur, next, lane_off, p.inv_S, xa, acc_a, acc_b);
+            lds_gbar[(q - R) * kFThreads + tid] =
+                fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
             cur = next;
         }
-        fused_regs_phase1<HG, NH, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        fused_regs_phase1<HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 
     // workgroup partial -> fixed slot
@@ -1119,13 +1124,17 @@ constexpr int kFRegChoices[] = {0, 10, 20, kFRegTiles};
 template <int R, bool LAG>
 const void *fused_kernel_for_r(int S)
 {
+#define KF(HG, NH, MASK) reinterpret_cast<const void *>(k_fused<HG, NH, MASK, R, LAG>)
     switch (S) {
-    case 2: return reinterpret_cast<const void *>(k_fused<1, 2, R, LAG>);
-    case 4: return reinterpret_cast<const void *>(k_fused<2, 2, R, LAG>);
-    case 8: return reinterpret_cast<const void *>(k_fused<4, 2, R, LAG>);
-    case 16: return reinterpret_cast<const void *>(k_fused<4, 4, R, LAG>);
-    default: return nullptr;
+    case 1: return KF(1, 2, true);
+    case 2: return KF(1, 2, false);
+    case 3: return KF(2, 2, true);
+    case 4: return KF(2, 2, false);
+    case 8: return KF(4, 2, false);
+    case 16: return KF(4, 4, false);
+    default: return S < 8 ? KF(4, 2, true) : S < 16 ? KF(4, 4, true) : nullptr;
     }
+#undef KF
 }
 
 // The fused kernel instance for scale S, R register slots and gain variant (nullptr: none, use
@@ -1174,7 +1183,7 @@ int setup_fused(adascale_ctx *c)
     const double need = env_int("ADASCALE_FUSED_MIN_PCT", 50) / 100.0;
     if (on_chip < need) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
-    for (int S : {2, 4, 8, 16}) {
+    for (int S = 1; S <= 16; ++S) {
         const void *fn = fused_kernel_for(S, regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
@@ -1519,6 +1528,13 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
                 }
                 fprintf(stderr, "stamp %d: min %.2f us  mean %.2f us  max %.2f us\n", j, mn / 100.0, sum / c->f_grid / 100.0, mx / 100.0);
             }
+            for (int x = 0; x < 8; ++x) {
+                double s2 = 0, s4 = 0; int n = 0;
+                for (int i = x; i < c->f_grid; i += 8) { s2 += h[8 * i + 2] - t0; s4 += (h[8 * i + 4] - h[8 * i + 3]); ++n; }
+                fprintf(stderr, "xcd %d: phase1 end mean %.2f us, phase2 mean %.2f us\n", x, s2 / n / 100.0, s4 / n / 100.0);
+            }
+            for (int i = 0; i < 32; ++i) fprintf(stderr, "%.0f ", (h[8 * i + 2] - t0) / 100.0);
+            fprintf(stderr, "\n");
         }
 #endif
         void *args[] = {&fa};

@@ -31,7 +31,7 @@ def step_path(request, monkeypatch):
 
 
 def expect_path(gpu, step_path, dtype=F32):
-    assert gpu.uses_fused_step() == (step_path == "fused" and dtype == F32)
+    assert gpu.uses_fused_step() == (step_path == "fused" and dtype == F32 and gpu.S <= 16)
 
 
 # ------------------------------------------------------------------ small shapes, every path
@@ -48,7 +48,7 @@ def test_small_multi_tensor_all_scales(S, dtype):
     H.assert_report(rep)
 
 
-@pytest.mark.parametrize("S", [2, 4, 8, 16])
+@pytest.mark.parametrize("S", [1, 2, 3, 4, 7, 8, 13, 16])
 def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, step_path, monkeypatch):
     """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
     if step_path != "fused":
