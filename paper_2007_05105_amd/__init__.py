@@ -4,5 +4,7 @@ kernels; this package only marshals arguments."""
 from .binding import (AdaScale, AdaScaleError, State, BF16, COOPERATIVE_LAUNCH, EST_NORM_RATIO, F32, LAGGED_R,
                       NO_POINTER_CHECK, library_path, load_library)
 
-__all__ = ["AdaScale", "AdaScaleError", "State", "F32", "BF16", "LAGGED_R", "EST_NORM_RATIO",
+from .driver import run_until_done
+
+__all__ = ["run_until_done", "AdaScale", "AdaScaleError", "State", "F32", "BF16", "LAGGED_R", "EST_NORM_RATIO",
            "NO_POINTER_CHECK", "COOPERATIVE_LAUNCH", "library_path", "load_library"]

@@ -1,0 +1,76 @@
+"""Dataset-free end-to-end run: a noisy quadratic (PL, smooth, bounded gradient variance: the
+setting of Theorems 1-2) trained with AdaScale at several scales until tau >= T_SI.  Checks the
+driver loop and stopping rule, the iteration bounds of Sec. 3.2, that the final objective does
+not degrade with S (the scale-invariance claim), and agreement with the CPU oracle fed the same
+gradients."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle.oracle import Oracle
+from paper_2007_05105_amd import AdaScale, run_until_done
+
+pytestmark = pytest.mark.gpu
+
+D, L = 20000, 400
+
+
+def problem():
+    rng = np.random.default_rng(0)
+    h = torch.tensor(rng.uniform(0.5, 2.0, D), dtype=torch.float32, device="cuda:0")
+    c = torch.tensor(rng.normal(size=D), dtype=torch.float32, device="cuda:0")
+    lr = W.lr_exponential_decay(0.05, L, 0.1)
+    return h, c, lr
+
+
+def train(S, with_oracle):
+    h, c, lr = problem()
+    w = [torch.zeros(D, device="cuda:0")]
+    v = [torch.zeros(D, device="cuda:0")]
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(100 + S)
+    ada = AdaScale([D], S, lr, momentum=0.9)
+    orc = Oracle(S, lr, momentum=0.9) if with_oracle else None
+    w64, v64 = [np.zeros(D)], [np.zeros(D)]
+    grads = [[torch.empty(D, device="cuda:0")] for _ in range(S)]
+    log = []
+
+    def make_grads(t):
+        base = h * (w[0] - c)                      # gradient of 0.5 * sum h (w - c)^2 at the current w
+        for i in range(S):
+            grads[i][0].copy_(base + torch.randn(D, generator=gen, device="cuda:0"))
+        return grads
+
+    def on_step(t, st):
+        if orc is not None:
+            ost = orc.step(w64, v64, [[g[0].cpu().numpy()] for g in grads])
+            log.append((st.r, ost.r, st.tau, ost.tau, st.done, ost.done))
+
+    steps = run_until_done(ada, w, v, make_grads, max_steps=L + 5, on_step=on_step)
+    st = ada.get_state()
+    loss = float(0.5 * torch.sum(h * (w[0] - c) ** 2))
+    ada.close()
+    return steps, loss, st, log, (w[0].cpu().numpy(), w64[0])
+
+
+def test_noisy_quadratic_reaches_t_si_at_every_scale():
+    h, c, _ = problem()
+    f0 = float(0.5 * torch.sum(h * c ** 2))
+    results = {S: train(S, with_oracle=(S in (1, 16))) for S in (1, 4, 16)}
+    steps = {S: r[0] for S, r in results.items()}
+    loss = {S: r[1] for S, r in results.items()}
+    print("iterations", steps, "final objective", loss, "initial", f0, flush=True)
+    for S, (n, f, st, log, (w_gpu, w_or)) in results.items():
+        assert st.done and st.tau >= L
+        assert math.ceil(L / S) <= n <= L                        # iteration bounds, Sec. 3.2
+        assert st.tau - st.r < L                                 # stopped at the first iteration past T_SI
+        assert f < 0.05 * f0
+        for r_gpu, r_or, tau_gpu, tau_or, d_gpu, d_or in log:    # same gradients into the oracle
+            assert abs(r_gpu - r_or) <= 1e-5 * r_or and abs(tau_gpu - tau_or) <= 1e-5 * tau_or and d_gpu == d_or
+        if log:
+            assert np.abs(w_gpu - w_or).max() <= 2e-5 * np.abs(w_or).max()
+    assert steps[1] == L and steps[1] > steps[4] > steps[16]     # S = 1: r = 1, tau = t
+    assert loss[4] <= 1.1 * loss[1] and loss[16] <= 1.1 * loss[1]   # quality does not degrade with scale

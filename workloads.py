@@ -112,6 +112,12 @@ def lr_step_decay(lr0: float, length: int, drops: Sequence[float] = (0.5, 0.75),
     return lr.astype(np.float32)
 
 
+def lr_exponential_decay(lr0: float, length: int, decay: float) -> np.ndarray:
+    """Exponential decay (App. B.1 form): lr0 * decay^(t / T)."""
+    j = np.arange(length, dtype=np.float64)
+    return (lr0 * decay ** (j / length)).astype(np.float32)
+
+
 def lr_inverse_sqrt(lr0: float, length: int, warm: int = 100) -> np.ndarray:
     j = np.arange(length, dtype=np.float64)
     return (lr0 * np.sqrt(warm / np.maximum(j + 1, warm))).astype(np.float32)
