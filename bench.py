@@ -1,7 +1,7 @@
 """Benchmark of the AdaScale step on one MI355X.
 
-`python bench.py --gpus 1 --steps K --warmup W` times K whole adascale_step calls (all three
-kernels: reduce, scalars, update) on synthetic gradients already resident in HBM and prints ONE
+`python bench.py --gpus 1 --steps K --warmup W` times K whole adascale_step calls (mean gradient
+and norms, scalars, update: one fused kernel or three) on synthetic gradients already resident in HBM and prints ONE
 JSON line.  The workload is the configuration the headline metric is quoted on: d = 25,557,032
 parameters in 161 tensors (bottleneck-CNN-like shapes), S = 16 fp32 gradient buffers.
 
@@ -9,7 +9,7 @@ value        = gradient bytes streamed per second (S*d*4 / step time), GB/s
 roofline     = the dominant kernel against the 8 TB/s HBM peak, algorithmic bytes of one launch /
                its average duration from HIP events on the launch stream inside the timed region:
                the fused step kernel (whole step, S*d*4 + 24*d bytes) when the library runs the
-               step as one cooperative launch, else the reduce kernel (S*d*4 read + 4*d written)
+               step as one persistent launch, else the reduce kernel (S*d*4 read + 4*d written)
 cpu_baseline = the CPU oracle (OpenMP build of the same source) on the host, one step of the
                same workload
 """
@@ -90,7 +90,7 @@ def main() -> int:
     # Per-kernel HIP events (recorded by the library on the launch stream) for the three-kernel
     # step.  The fused step is a single kernel per step: one pair of events on the launch stream
     # around the K launches gives its average duration without putting an event between every
-    # two cooperative launches.
+    # two launches.
     events = not args.no_kernel_events and not fused
     if events:
         gpu.profile_begin(args.steps)

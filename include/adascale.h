@@ -152,8 +152,8 @@ const char *adascale_last_error(const adascale_ctx *ctx);
  * per-parameter traffic of the mean gradient, w and v.  For benchmarks; host only. */
 int64_t adascale_step_bytes(const adascale_ctx *ctx);
 
-/* 1 if this context runs the step as one fused cooperative launch that keeps the mean gradient
- * on chip (fp32 gradients whose mean gradient mostly fits in registers + LDS), 0 if it runs the
+/* 1 if this context runs the step as one fused persistent launch that keeps the mean gradient
+ * on chip (fp32 gradients, S <= 16, mean gradient mostly fitting in registers + LDS), 0 if it runs the
  * three-kernel step (reduce, scalars, update).  Both compute the same thing. */
 int adascale_uses_fused_step(const adascale_ctx *ctx);
 

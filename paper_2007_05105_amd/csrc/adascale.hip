@@ -544,7 +544,7 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
 }
 
 // ---------------------------------------------------------------------------------------------
-// fused step: one persistent cooperative launch, one workgroup per compute unit.
+// fused step: one persistent launch, one workgroup per compute unit.
 //
 // Writing the mean gradient to HBM between the two passes is what the three-kernel step pays
 // most for: a small write stream mixed into the gradient reads lowers the read rate of the whole
@@ -588,70 +588,144 @@ struct FLoc {
     unsigned long long tile_off;
 };
 
+// How the fused kernel fetches and accumulates a lane's 4 gradient elements of one replica.
+// fp32: one 16-byte load, fp64 accumulation (squares of fp32 values are not exact in fp32).
+// bf16: one 8-byte load, fp32 accumulation flushed to fp64 after every half-group (products of
+// bf16 values are exact in fp32; see the reduce kernel for the argument).
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+typedef u2 u2e __attribute__((aligned(2)));
+
+template <typename GT>
+struct FGrad;
+
+template <>
+struct FGrad<float> {
+    typedef f4 raw;
+    static constexpr int kShift = 0;  // gradient byte offset = fp32 byte offset >> kShift
+    static __device__ __forceinline__ raw load(gp_cchar p) { return __builtin_nontemporal_load((gp_cf4)p); }
+    static __device__ __forceinline__ raw load_partial(gp_cchar p, int c4)
+    {
+        const AS_GLOBAL float *e = (const AS_GLOBAL float *)p;
+        raw x = {e[0], 0.f, 0.f, 0.f};
+        if (c4 > 1) x.y = e[1];
+        if (c4 > 2) x.z = e[2];
+        return x;
+    }
+    struct Acc {
+        double s[4], a;
+        __device__ __forceinline__ void init() { s[0] = s[1] = s[2] = s[3] = 0.0; a = 0.0; }
+        __device__ __forceinline__ void add(raw x, bool live)
+        {
+            const float xv[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double xd = live ? (double)xv[e] : 0.0;
+                s[e] += xd;
+                a = fma(xd, xd, a);
+            }
+        }
+        __device__ __forceinline__ void flush() {}
+        __device__ __forceinline__ double sum(int e) const { return s[e]; }
+    };
+};
+
+template <>
+struct FGrad<Bf16> {
+    typedef u2 raw;
+    static constexpr int kShift = 1;
+    static __device__ __forceinline__ raw load(gp_cchar p) { return __builtin_nontemporal_load((const AS_GLOBAL u2e *)p); }
+    static __device__ __forceinline__ raw load_partial(gp_cchar p, int c4)
+    {
+        const AS_GLOBAL unsigned short *e = (const AS_GLOBAL unsigned short *)p;
+        raw x = {(unsigned)e[0], 0u};
+        if (c4 > 1) x.x |= (unsigned)e[1] << 16;
+        if (c4 > 2) x.y = (unsigned)e[2];
+        return x;
+    }
+    struct Acc {
+        float s[4], af;
+        double a;
+        __device__ __forceinline__ void init() { s[0] = s[1] = s[2] = s[3] = 0.f; af = 0.f; a = 0.0; }
+        __device__ __forceinline__ void add(raw x, bool live)
+        {
+            const unsigned w[2] = {x.x, x.y};
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float lo = live ? __uint_as_float(w[j] << 16) : 0.f;
+                const float hi = live ? __uint_as_float(w[j] & 0xffff0000u) : 0.f;
+                s[2 * j] += lo;
+                s[2 * j + 1] += hi;
+                af = fmaf(lo, lo, af);
+                af = fmaf(hi, hi, af);
+            }
+        }
+        __device__ __forceinline__ void flush() { a += (double)af; af = 0.f; }
+        __device__ __forceinline__ double sum(int e) const { return (double)s[e]; }
+    };
+};
+
 // A tile's S = HG * NH replicas are consumed in NH (even) half-groups of HG replicas, alternating
-// between two register buffers: while one half-group is accumulated in fp64, the loads of the
-// next one (of the same tile, or of the next tile after the last half-group) are in flight.
+// between two register buffers: while one half-group is accumulated, the loads of the next one
+// (of the same tile, or of the next tile after the last half-group) are in flight.
 // MASK: S may be smaller than HG * NH; replica slots at or past S re-read the last replica (no
 // branch, the line is already on its way) and count as zero when accumulated.
-template <int HG, bool MASK>
-__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, int S, f4 (&x)[HG])
+template <typename GT, int HG, bool MASK>
+__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, int S,
+                                            typename FGrad<GT>::raw (&x)[HG])
 {
 #pragma unroll
     for (int g = 0; g < HG; ++g) {
         const int i = MASK ? min(first + g, S - 1) : first + g;
-        x[g] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowG + i] + L.tile_off) + lane_off));
+        x[g] = FGrad<GT>::load((gp_cchar)(L.row[kRowG + i] + (L.tile_off >> FGrad<GT>::kShift)) +
+                               (lane_off >> FGrad<GT>::kShift));
     }
 }
 
-template <int HG, bool MASK>
-__device__ __forceinline__ void fused_accumulate(const f4 (&x)[HG], int first, int S, double (&s)[4], double &a)
+template <typename GT, int HG, bool MASK>
+__device__ __forceinline__ void fused_accumulate(const typename FGrad<GT>::raw (&x)[HG], int first, int S,
+                                                 typename FGrad<GT>::Acc &acc)
 {
 #pragma unroll
     for (int g = 0; g < HG; ++g) {
-        const bool live = !MASK || first + g < S;
-        const float xv[4] = {x[g].x, x[g].y, x[g].z, x[g].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const double xd = live ? (double)xv[e] : 0.0;
-            s[e] += xd;
-            a = fma(xd, xd, a);
-        }
-        // keep the replicas in order: hoisting all fp32 -> fp64 conversions costs 2 VGPRs each
+        acc.add(x[g], !MASK || first + g < S);
+        // keep the replicas in order: hoisting all the conversions costs registers
         __builtin_amdgcn_sched_barrier(0);
     }
+    acc.flush();
 }
 
 // Mean gradient of one full tile plus its contribution to A and B.  On entry `xa` holds (in
 // flight) half-group 0 of this tile; on return half-group 0 of the NEXT tile is in flight there
-// (the last tile of a workgroup names itself as next: 16 redundant loads, no branch).
-template <int HG, int NH, bool MASK>
+// (the last tile of a workgroup names itself as next: a few redundant loads, no branch).
+template <typename GT, int HG, int NH, bool MASK>
 __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, int S, double inv_S,
-                                              f4 (&xa)[HG], double &acc_a, double &acc_b)
+                                              typename FGrad<GT>::raw (&xa)[HG], double &acc_a, double &acc_b)
 {
     static_assert(NH % 2 == 0, "half-groups alternate between two buffers");
-    double s[4] = {0.0, 0.0, 0.0, 0.0};
-    double a = 0.0, b = 0.0;
-    f4 xb[HG];
+    typename FGrad<GT>::Acc acc;
+    acc.init();
+    typename FGrad<GT>::raw xb[HG];
 #pragma unroll
     for (int h = 0; h < NH; h += 2) {
-        fused_issue<HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
+        fused_issue<GT, HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
-        fused_accumulate<HG, MASK>(xa, h * HG, S, s, a);
+        fused_accumulate<GT, HG, MASK>(xa, h * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
-        if (h + 2 < NH) fused_issue<HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
-        else fused_issue<HG, MASK>(next, lane_off, 0, S, xa);
+        if (h + 2 < NH) fused_issue<GT, HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
+        else fused_issue<GT, HG, MASK>(next, lane_off, 0, S, xa);
         __builtin_amdgcn_sched_barrier(0);
-        fused_accumulate<HG, MASK>(xb, (h + 1) * HG, S, s, a);
+        fused_accumulate<GT, HG, MASK>(xb, (h + 1) * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
     }
     float o[4];
+    double b = 0.0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const double m = s[e] * inv_S;
+        const double m = acc.sum(e) * inv_S;
         o[e] = (float)m;
         b = fma(m, m, b);
     }
-    acc_a += a;
+    acc_a += acc.a;
     acc_b += b;
     // Keep the 8 waves of the workgroup on the same tile: left alone, the older waves win the
     // arbitration for the memory pipeline and the workgroup then waits for its youngest wave.
@@ -710,7 +784,7 @@ struct FusedArgs {
 // Ragged last tile of a tensor, phase 1: per-lane predicates, mean gradient to the HBM scratch.
 // Lanes wholly inside the tensor use one 16-byte load per replica, the lane on the boundary
 // single elements; the replicas are loaded HG at a time so that their latencies overlap.
-template <int HG, int NH>
+template <typename GT, int HG>
 __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int tid, double &acc_a, double &acc_b)
 {
     const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
@@ -720,28 +794,23 @@ __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int t
     const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
     if (rem <= 0) return;
     const int c4 = rem < 4 ? (int)rem : 4;
-    double s[4] = {0.0, 0.0, 0.0, 0.0};
-    double a = 0.0, b = 0.0;
+    typename FGrad<GT>::Acc acc;
+    acc.init();
     for (int i0 = 0; i0 < p.S; i0 += HG) {
-        f4 x[HG];
+        typename FGrad<GT>::raw x[HG];
 #pragma unroll
         for (int g = 0; g < HG; ++g) {
-            const AS_GLOBAL float *gp = (const AS_GLOBAL float *)row[kRowG + min(i0 + g, p.S - 1)] + first;
-            if (c4 == 4) {
-                x[g] = __builtin_nontemporal_load((gp_cf4)gp);
-            } else {
-                x[g] = f4{gp[0], 0.f, 0.f, 0.f};
-                if (c4 > 1) x[g].y = gp[1];
-                if (c4 > 2) x[g].z = gp[2];
-            }
+            gp_cchar gp = (gp_cchar)row[kRowG + min(i0 + g, p.S - 1)] + ((first * 4) >> FGrad<GT>::kShift);
+            x[g] = c4 == 4 ? FGrad<GT>::load(gp) : FGrad<GT>::load_partial(gp, c4);
         }
-        fused_accumulate<HG, true>(x, i0, p.S, s, a);
+        fused_accumulate<GT, HG, true>(x, i0, p.S, acc);
     }
     AS_GLOBAL float *gb = (AS_GLOBAL float *)row[kRowGbar] + first;
     float o[4];
+    double b = 0.0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const double m = s[e] * p.inv_S;   // elements past the end were loaded as zeros: m = 0
+        const double m = acc.sum(e) * p.inv_S;   // elements past the end were loaded as zeros: m = 0
         o[e] = (float)m;
         b = fma(m, m, b);
     }
@@ -752,7 +821,7 @@ __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int t
         if (c4 > 1) gb[1] = o[1];
         if (c4 > 2) gb[2] = o[2];
     }
-    acc_a += a;
+    acc_a += acc.a;
     acc_b += b;
 }
 
@@ -819,15 +888,16 @@ struct FCtx {
 
 // Register slots, addressed at compile time (template recursion instead of a loop so that the
 // retained values are plain registers whatever the unroller decides).
-template <int HG, int NH, bool MASK, int R, int Q>
+template <typename GT, int HG, int NH, bool MASK, int R, int Q>
 __device__ __forceinline__ void fused_regs_phase1(const FCtx<R> &cx, unsigned lane_off, f4 (&keep)[R > 0 ? R : 1],
-                                                  FLoc &cur, f4 (&xa)[HG], double &acc_a, double &acc_b)
+                                                  FLoc &cur, typename FGrad<GT>::raw (&xa)[HG], double &acc_a,
+                                                  double &acc_b)
 {
     if constexpr (Q < R) {
         const FLoc next = cx.locate(cx.after(Q));
-        keep[Q] = fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, cx.p.S, cx.p.inv_S, xa, acc_a, acc_b);
+        keep[Q] = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, cx.p.S, cx.p.inv_S, xa, acc_a, acc_b);
         cur = next;
-        fused_regs_phase1<HG, NH, MASK, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        fused_regs_phase1<GT, HG, NH, MASK, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 }
 
@@ -844,7 +914,7 @@ __device__ __forceinline__ void fused_regs_phase2(const FCtx<R> &cx, unsigned la
 // S == HG * NH (MASK: S <= HG * NH); R = register slots per lane (every workgroup has at least R full tiles).
 // LAG: prior-iteration gain (App. B.3) -- eta_t is known at the start, so there is no grid
 // barrier and no scalar evaluation here; k_scalars runs afterwards on the partials.
-template <int HG, int NH, bool MASK, int R, bool LAG>
+template <typename GT, int HG, int NH, bool MASK, int R, bool LAG>
 __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 {
     extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
@@ -863,27 +933,27 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 
     // phase 1
     FUSED_STAMP(0);
-    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<HG, NH>(p, c, tid, acc_a, acc_b);
+    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG>(p, c, tid, acc_a, acc_b);
     FUSED_STAMP(1);
 
     if (n_valid > 0) {
-        f4 xa[HG];
+        typename FGrad<GT>::raw xa[HG];
         const int q_first = q_hbm < n_valid ? q_hbm : (R < q_lds_end ? R : 0);
         FLoc cur = cx.locate(q_first);
-        fused_issue<HG, MASK>(cur, lane_off, 0, p.S, xa);
+        fused_issue<GT, HG, MASK>(cur, lane_off, 0, p.S, xa);
         for (int q = q_hbm; q < n_valid; ++q) {
             const FLoc next = cx.locate(cx.after(q));
-            const f4 m = fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+            const f4 m = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
             *(gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off) = m;
             cur = next;
         }
         for (int q = R; q < q_lds_end; ++q) {
             const FLoc next = cx.locate(cx.after(q));
             lds_gbar[(q - R) * kFThreads + tid] =
-                fused_tile_mean<HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+                fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
             cur = next;
         }
-        fused_regs_phase1<HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
+        fused_regs_phase1<GT, HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 
     // workgroup partial -> fixed slot
@@ -1119,44 +1189,54 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
 
 // Register-slot counts the fused kernel is instantiated for; the host uses the largest one that
 // every workgroup can fill.
-constexpr int kFRegChoices[] = {0, 10, 20, kFRegTiles};
+constexpr int kFRegChoices[] = {0, 10, kFRegTiles};
+constexpr int kFMaxScaleF32 = 16, kFMaxScaleBf16 = 32;
 
 template <int R, bool LAG>
-const void *fused_kernel_for_r(int S)
+const void *fused_kernel_for_r(int dtype, int S)
 {
-#define KF(HG, NH, MASK) reinterpret_cast<const void *>(k_fused<HG, NH, MASK, R, LAG>)
-    switch (S) {
-    case 1: return KF(1, 2, true);
-    case 2: return KF(1, 2, false);
-    case 3: return KF(2, 2, true);
-    case 4: return KF(2, 2, false);
-    case 8: return KF(4, 2, false);
-    case 16: return KF(4, 4, false);
-    default: return S < 8 ? KF(4, 2, true) : S < 16 ? KF(4, 4, true) : nullptr;
+#define KF(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_fused<GT, HG, NH, MASK, R, LAG>)
+    if (dtype == ADASCALE_F32) {  // 4-replica half-groups of 16-byte loads
+        switch (S) {
+        case 1: return KF(float, 1, 2, true);
+        case 2: return KF(float, 1, 2, false);
+        case 3: return KF(float, 2, 2, true);
+        case 4: return KF(float, 2, 2, false);
+        case 8: return KF(float, 4, 2, false);
+        case 16: return KF(float, 4, 4, false);
+        default: return S < 8 ? KF(float, 4, 2, true) : S < 16 ? KF(float, 4, 4, true) : nullptr;
+        }
     }
+    // bf16: 8-byte loads, so twice the replicas per half-group for the same bytes in flight
+    if (S <= 2) return KF(Bf16, 1, 2, true);
+    if (S <= 4) return KF(Bf16, 2, 2, true);
+    if (S <= 8) return KF(Bf16, 4, 2, true);
+    if (S <= 16) return KF(Bf16, 8, 2, true);
+    if (S <= 32) return KF(Bf16, 8, 4, true);
+    return nullptr;
 #undef KF
 }
 
-// The fused kernel instance for scale S, R register slots and gain variant (nullptr: none, use
-// the general step).
-const void *fused_kernel_for(int S, int R, bool lag)
+// The fused kernel instance for a gradient type, scale S, R register slots and gain variant
+// (nullptr: none, use the general step).
+const void *fused_kernel_for(int dtype, int S, int R, bool lag)
 {
     switch (R) {
-    case 0: return lag ? fused_kernel_for_r<0, true>(S) : fused_kernel_for_r<0, false>(S);
-    case 10: return lag ? fused_kernel_for_r<10, true>(S) : fused_kernel_for_r<10, false>(S);
-    case 20: return lag ? fused_kernel_for_r<20, true>(S) : fused_kernel_for_r<20, false>(S);
-    case kFRegTiles: return lag ? fused_kernel_for_r<kFRegTiles, true>(S) : fused_kernel_for_r<kFRegTiles, false>(S);
+    case 0: return lag ? fused_kernel_for_r<0, true>(dtype, S) : fused_kernel_for_r<0, false>(dtype, S);
+    case 10: return lag ? fused_kernel_for_r<10, true>(dtype, S) : fused_kernel_for_r<10, false>(dtype, S);
+    case kFRegTiles:
+        return lag ? fused_kernel_for_r<kFRegTiles, true>(dtype, S) : fused_kernel_for_r<kFRegTiles, false>(dtype, S);
     default: return nullptr;
     }
 }
 
 // Decide whether the fused single-launch step applies and build its tile tables.  It needs fp32
-// gradients, cooperative launch, and enough of the mean gradient to fit on chip to be worth it.
+// gradients, S <= 16, and enough of the mean gradient to fit on chip to be worth it.
 int setup_fused(adascale_ctx *c)
 {
     c->fused_ok = false;
     if (env_int("ADASCALE_FUSED", 1) == 2) return ADASCALE_OK;              // 2 = force the three-kernel step
-    if (c->cfg.grad_dtype != ADASCALE_F32 || c->d == 0) return ADASCALE_OK;
+    if (c->d == 0) return ADASCALE_OK;
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
     if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
@@ -1183,8 +1263,9 @@ int setup_fused(adascale_ctx *c)
     const double need = env_int("ADASCALE_FUSED_MIN_PCT", 50) / 100.0;
     if (on_chip < need) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
-    for (int S = 1; S <= 16; ++S) {
-        const void *fn = fused_kernel_for(S, regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
+    const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
+    for (int S = 1; S <= max_scale; ++S) {
+        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
@@ -1249,7 +1330,7 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
 
-int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.S, c->f_regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
+int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -1487,7 +1568,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
-    const void *fused_fn = c->fused_ok ? fused_kernel_for(S, c->f_regs, lag) : nullptr;
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_regs, lag) : nullptr;
     if (fused_fn) {
         FusedArgs fa{};
         fa.tiles = c->d_ftiles;

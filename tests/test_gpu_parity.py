@@ -23,15 +23,15 @@ def log(msg):
 
 @pytest.fixture(autouse=True, params=["fused", "three_kernel"])
 def step_path(request, monkeypatch):
-    """Every test runs once per implementation of the step: the fused cooperative launch (fp32
-    gradients; the library picks it when enough of the mean gradient fits on chip) and the
-    three-kernel step (forced here; bf16 gradients always take it)."""
+    """Every test runs once per implementation of the step: the fused persistent launch (S <= 16
+    for fp32 gradients, <= 32 for bf16; the library picks it when enough of the mean gradient fits
+    on chip) and the three-kernel step (forced here)."""
     monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
     return request.param
 
 
 def expect_path(gpu, step_path, dtype=F32):
-    assert gpu.uses_fused_step() == (step_path == "fused" and dtype == F32 and gpu.S <= 16)
+    assert gpu.uses_fused_step() == (step_path == "fused" and gpu.S <= (16 if dtype == F32 else 32))
 
 
 # ------------------------------------------------------------------ small shapes, every path
@@ -48,14 +48,16 @@ def test_small_multi_tensor_all_scales(S, dtype):
     H.assert_report(rep)
 
 
-@pytest.mark.parametrize("S", [1, 2, 3, 4, 7, 8, 13, 16])
-def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, step_path, monkeypatch):
+@pytest.mark.parametrize("S,dtype", [(1, F32), (2, F32), (3, F32), (4, F32), (7, F32), (8, F32), (13, F32), (16, F32),
+                                     (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16)])
+def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, dtype, step_path, monkeypatch):
     """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
     if step_path != "fused":
         pytest.skip("fused step only")
     monkeypatch.setenv("ADASCALE_FUSED_GRID", "2")
     monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
-    wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, weight_decay=1e-3, theta=0.5, steps=3, seed=S)
+    wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5,
+                  steps=3, seed=S)
     g = H.make_gpu(wl)
     assert g.uses_fused_step()
     g.close()
@@ -303,7 +305,7 @@ def test_config3_benchmark_shape(step_path):
 @pytest.mark.timeout(900)
 def test_config4_bf16(step_path):
     if step_path == "fused":
-        pytest.skip("bf16 gradients always take the three-kernel step")
+        pytest.skip("the mean gradient of this configuration does not fit on chip: same path as three_kernel")
     wl = W.config(4)
     rep = H.run_teacher_forced(wl, n_steps=4, check_steps=[0, 3], openmp=True, log=log)
     H.assert_report(rep)
@@ -314,7 +316,7 @@ def test_config5_bf16_45GB(step_path):
     """d = 351M, S = 64: 45 GB of bf16 gradients resident; the oracle (OpenMP build) checks two
     steps of the signal-to-noise sweep, one noise dominated and one signal dominated."""
     if step_path == "fused":
-        pytest.skip("bf16 gradients always take the three-kernel step")
+        pytest.skip("the mean gradient of this configuration does not fit on chip: same path as three_kernel")
     wl = W.config(5)
     inp = W.Inputs(wl, "cuda:0")
     rep = H.run_teacher_forced(wl, n_steps=2, check_steps=[0, 1], openmp=True, inputs=inp, log=log)
