@@ -705,7 +705,9 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     typename FGrad<GT>::Acc acc;
     acc.init();
     typename FGrad<GT>::raw xb[HG];
-#pragma unroll
+    // eight half-groups stay a loop: unrolled they cost more registers than there are
+    constexpr int kUnroll = NH > 4 ? 1 : NH;
+#pragma unroll kUnroll
     for (int h = 0; h < NH; h += 2) {
         fused_issue<GT, HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
@@ -1097,7 +1099,7 @@ struct adascale_ctx {
     FTile *d_ftiles = nullptr, *d_ctiles = nullptr;
     unsigned long long *d_barrier = nullptr;
     unsigned long long fused_launches = 0;
-    int f_grid = 0, f_tpb = 0, f_lds_tiles = 0, f_regs = 0;
+    int f_grid = 0, f_tpb = 0, f_lds_cap = 0, f_level = 0;
     bool fused_ok = false;
 
     DevState *h_state = nullptr;    // pinned
@@ -1187,45 +1189,69 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
     return a >= lo && a + bytes <= hi;
 }
 
-// Register-slot counts the fused kernel is instantiated for; the host uses the largest one that
-// every workgroup can fill.
-constexpr int kFRegChoices[] = {0, 10, kFRegTiles};
-constexpr int kFMaxScaleF32 = 16, kFMaxScaleBf16 = 32;
+// Register-slot counts the fused kernel is instantiated for (the host uses the largest one that
+// every workgroup can fill): three levels, the top one lower for the instances with eight
+// half-groups, which need the registers themselves.
+constexpr int kFRegLevels = 3;
+constexpr int fused_regs_at(int level, int nh) { return level == 0 ? 0 : level == 1 ? 10 : nh > 4 ? 20 : kFRegTiles; }
+constexpr int kFMaxScaleF32 = 32, kFMaxScaleBf16 = 64;
 
-template <int R, bool LAG>
-const void *fused_kernel_for_r(int dtype, int S)
+// Half-group shape (HG, NH) for a gradient type and scale; false: no instance.
+bool fused_shape(int dtype, int S, int *hg, int *nh)
 {
-#define KF(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_fused<GT, HG, NH, MASK, R, LAG>)
-    if (dtype == ADASCALE_F32) {  // 4-replica half-groups of 16-byte loads
-        switch (S) {
-        case 1: return KF(float, 1, 2, true);
-        case 2: return KF(float, 1, 2, false);
-        case 3: return KF(float, 2, 2, true);
-        case 4: return KF(float, 2, 2, false);
-        case 8: return KF(float, 4, 2, false);
-        case 16: return KF(float, 4, 4, false);
-        default: return S < 8 ? KF(float, 4, 2, true) : S < 16 ? KF(float, 4, 4, true) : nullptr;
+    if (S < 1 || S > (dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16)) return false;
+    // fp32: half-groups of up to 4 16-byte loads; bf16: 8-byte loads, so twice the replicas per
+    // half-group for the same bytes in flight
+    const int cap = dtype == ADASCALE_F32 ? 4 : 8;
+    int h = 1;
+    while (h < cap && 2 * h < S) h *= 2;  // smallest HG with 2 * HG >= S, at most cap
+    int n = 2;
+    while (h * n < S) n *= 2;
+    *hg = h;
+    *nh = n;
+    return true;
+}
+
+template <int LEVEL, bool LAG>
+const void *fused_kernel_at(int dtype, int S)
+{
+#define KF(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_fused<GT, HG, NH, MASK, fused_regs_at(LEVEL, NH), LAG>)
+    int hg = 0, nh = 0;
+    if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
+    const bool exact = hg * nh == S;
+    if (dtype == ADASCALE_F32) {
+        switch (hg * 100 + nh) {
+        case 102: return exact ? KF(float, 1, 2, false) : KF(float, 1, 2, true);
+        case 202: return exact ? KF(float, 2, 2, false) : KF(float, 2, 2, true);
+        case 402: return exact ? KF(float, 4, 2, false) : KF(float, 4, 2, true);
+        case 404: return exact ? KF(float, 4, 4, false) : KF(float, 4, 4, true);
+        case 408: return KF(float, 4, 8, true);
+        default: return nullptr;
         }
     }
-    // bf16: 8-byte loads, so twice the replicas per half-group for the same bytes in flight
-    if (S <= 2) return KF(Bf16, 1, 2, true);
-    if (S <= 4) return KF(Bf16, 2, 2, true);
-    if (S <= 8) return KF(Bf16, 4, 2, true);
-    if (S <= 16) return KF(Bf16, 8, 2, true);
-    if (S <= 32) return KF(Bf16, 8, 4, true);
-    return nullptr;
+    switch (hg * 100 + nh) {
+    case 102: return KF(Bf16, 1, 2, true);
+    case 202: return KF(Bf16, 2, 2, true);
+    case 402: return KF(Bf16, 4, 2, true);
+    case 802: return KF(Bf16, 8, 2, true);
+    case 804: return KF(Bf16, 8, 4, true);
+    case 808: return KF(Bf16, 8, 8, true);
+    default: return nullptr;
+    }
 #undef KF
 }
 
-// The fused kernel instance for a gradient type, scale S, R register slots and gain variant
-// (nullptr: none, use the general step).
-const void *fused_kernel_for(int dtype, int S, int R, bool lag)
+// The fused kernel instance for a gradient type, scale S, register-slot level and gain variant
+// (nullptr: none, use the general step), and the number of register slots it keeps.
+const void *fused_kernel_for(int dtype, int S, int level, bool lag, int *regs = nullptr)
 {
-    switch (R) {
-    case 0: return lag ? fused_kernel_for_r<0, true>(dtype, S) : fused_kernel_for_r<0, false>(dtype, S);
-    case 10: return lag ? fused_kernel_for_r<10, true>(dtype, S) : fused_kernel_for_r<10, false>(dtype, S);
-    case kFRegTiles:
-        return lag ? fused_kernel_for_r<kFRegTiles, true>(dtype, S) : fused_kernel_for_r<kFRegTiles, false>(dtype, S);
+    int hg = 0, nh = 0;
+    if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
+    if (regs) *regs = fused_regs_at(level, nh);
+    switch (level) {
+    case 0: return lag ? fused_kernel_at<0, true>(dtype, S) : fused_kernel_at<0, false>(dtype, S);
+    case 1: return lag ? fused_kernel_at<1, true>(dtype, S) : fused_kernel_at<1, false>(dtype, S);
+    case 2: return lag ? fused_kernel_at<2, true>(dtype, S) : fused_kernel_at<2, false>(dtype, S);
     default: return nullptr;
     }
 }
@@ -1254,18 +1280,19 @@ int setup_fused(adascale_ctx *c)
     const int cus = std::min(std::min(prop.multiProcessorCount, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
     const int grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
     const int tpb = (int)((nt + grid - 1) / grid);
-    int regs = 0;  // register slots: the largest choice every workgroup can fill
-    for (int r : kFRegChoices)
-        if (r <= nt / grid) regs = r;
+    int level = 0;  // register-slot level: the highest whose (largest) slot count every workgroup can fill
+    for (int l = 0; l < kFRegLevels; ++l)
+        if (fused_regs_at(l, 2) <= nt / grid) level = l;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
-    const int lds_tiles = std::max(0, std::min(tpb - regs, lds_cap));
-    const double on_chip = tpb == 0 ? 1.0 : std::min(1.0, (double)(regs + lds_tiles) / tpb);
-    const double need = env_int("ADASCALE_FUSED_MIN_PCT", 50) / 100.0;
-    if (on_chip < need) return ADASCALE_OK;
-    const size_t lds_bytes = (size_t)lds_tiles * kFThreads * sizeof(f4);
+    // the fused step pays as soon as part of the mean gradient stays on chip (12 % faster with
+    // half of it there, 3 % with a tenth); the percentage is a development knob
+    const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level, 2) + std::min(tpb, lds_cap)) / tpb);
+    if (on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", 0)) return ADASCALE_OK;
+    const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
     const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
     for (int S = 1; S <= max_scale; ++S) {
-        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
+        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
+        if (!fn) continue;
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
@@ -1277,8 +1304,8 @@ int setup_fused(adascale_ctx *c)
     if (nc) HIP_TRY(c, hipMemcpy(c->d_ctiles, c->ctiles.data(), sizeof(FTile) * nc, hipMemcpyHostToDevice));
     c->f_grid = grid;
     c->f_tpb = tpb;
-    c->f_lds_tiles = lds_tiles;
-    c->f_regs = regs;
+    c->f_lds_cap = lds_cap;
+    c->f_level = level;
     c->fused_ok = true;
     return ADASCALE_OK;
 }
@@ -1330,7 +1357,7 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
 
-int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_regs, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
+int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -1568,7 +1595,9 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
-    const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_regs, lag) : nullptr;
+    int f_regs = 0;
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag, &f_regs) : nullptr;
+    const int f_lds_tiles = std::max(0, std::min(c->f_tpb - f_regs, c->f_lds_cap));
     if (fused_fn) {
         FusedArgs fa{};
         fa.tiles = c->d_ftiles;
@@ -1585,7 +1614,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.fault = c->d_fault;
         fa.n_tiles = (int)c->ftiles.size();
         fa.tiles_per_block = c->f_tpb;
-        fa.lds_tiles = c->f_lds_tiles;
+        fa.lds_tiles = f_lds_tiles;
         fa.S = S;
         fa.inv_S = 1.0 / (double)S;
         fa.rho = (float)c->cfg.momentum;
@@ -1619,7 +1648,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         }
 #endif
         void *args[] = {&fa};
-        const size_t lds_bytes = (size_t)c->f_lds_tiles * kFThreads * sizeof(f4);
+        const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
         if (c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) {
             HIP_TRY(c, hipLaunchCooperativeKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args, lds_bytes, s));
         } else {

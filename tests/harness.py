@@ -119,14 +119,17 @@ def tensor_err(gpu_flat: torch.Tensor, ref: List[np.ndarray], before: List[np.nd
 
 def run_teacher_forced(wl: W.Workload, check_steps: Optional[Iterable[int]] = None, n_steps: Optional[int] = None,
                        openmp: bool = False, flags: int = 0, skew_elems: int = 0, device: str = "cuda:0",
-                       inputs: Optional[W.Inputs] = None, log=None) -> RunReport:
-    n_steps = wl.steps if n_steps is None else n_steps
-    check = set(range(n_steps)) if check_steps is None else set(check_steps)
+                       inputs: Optional[W.Inputs] = None, step_ids: Optional[Iterable[int]] = None,
+                       log=None) -> RunReport:
+    """step_ids: which iterations' gradients to feed, in order (default 0 .. n_steps-1); all of
+    check_steps (default: every fed step) are compared with the oracle."""
+    ids = list(range(wl.steps if n_steps is None else n_steps)) if step_ids is None else list(step_ids)
+    check = set(ids) if check_steps is None else set(check_steps)
     inp = inputs if inputs is not None else W.Inputs(wl, device, skew_elems=skew_elems)
     gpu = make_gpu(wl, flags=flags)
     orc = make_oracle(wl, flags=flags, openmp=openmp)
     rep = RunReport()
-    for t in range(n_steps):
+    for t in ids:
         inp.fill_grads(t)
         if t not in check:
             gpu.step(inp.w, inp.v, inp.g)

@@ -23,15 +23,15 @@ def log(msg):
 
 @pytest.fixture(autouse=True, params=["fused", "three_kernel"])
 def step_path(request, monkeypatch):
-    """Every test runs once per implementation of the step: the fused persistent launch (S <= 16
-    for fp32 gradients, <= 32 for bf16; the library picks it when enough of the mean gradient fits
-    on chip) and the three-kernel step (forced here)."""
+    """Every test runs once per implementation of the step: the fused persistent launch (S <= 32
+    for fp32 gradients, <= 64 for bf16: the mean gradient stays on chip as far as it fits) and the
+    three-kernel step (forced here; also what larger scales get)."""
     monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
     return request.param
 
 
 def expect_path(gpu, step_path, dtype=F32):
-    assert gpu.uses_fused_step() == (step_path == "fused" and gpu.S <= (16 if dtype == F32 else 32))
+    assert gpu.uses_fused_step() == (step_path == "fused" and gpu.S <= (32 if dtype == F32 else 64))
 
 
 # ------------------------------------------------------------------ small shapes, every path
@@ -49,7 +49,8 @@ def test_small_multi_tensor_all_scales(S, dtype):
 
 
 @pytest.mark.parametrize("S,dtype", [(1, F32), (2, F32), (3, F32), (4, F32), (7, F32), (8, F32), (13, F32), (16, F32),
-                                     (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16)])
+                                     (23, F32), (32, F32),
+                                     (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16), (51, BF16), (64, BF16)])
 def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, dtype, step_path, monkeypatch):
     """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
     if step_path != "fused":
@@ -116,7 +117,7 @@ def test_variants_of_the_estimator(flags):
     H.assert_report(H.run_teacher_forced(wl, flags=flags, log=log))
 
 
-@pytest.mark.parametrize("S,dtype", [(16, F32), (4, F32), (32, BF16), (5, F32)])
+@pytest.mark.parametrize("S,dtype", [(16, F32), (4, F32), (32, BF16), (5, F32), (64, BF16), (29, F32), (40, F32)])
 def test_lagged_gain_single_pass_medium(S, dtype, step_path):
     """Prior-iteration gain on shapes that span many tiles per workgroup: the step is one sweep
     (reduce + update) followed by the scalar kernel."""
@@ -304,20 +305,21 @@ def test_config3_benchmark_shape(step_path):
 
 @pytest.mark.timeout(900)
 def test_config4_bf16(step_path):
-    if step_path == "fused":
-        pytest.skip("the mean gradient of this configuration does not fit on chip: same path as three_kernel")
     wl = W.config(4)
+    g = H.make_gpu(wl)
+    expect_path(g, step_path, BF16)
+    g.close()
     rep = H.run_teacher_forced(wl, n_steps=4, check_steps=[0, 3], openmp=True, log=log)
     H.assert_report(rep)
 
 
 @pytest.mark.timeout(1100)
 def test_config5_bf16_45GB(step_path):
-    """d = 351M, S = 64: 45 GB of bf16 gradients resident; the oracle (OpenMP build) checks two
-    steps of the signal-to-noise sweep, one noise dominated and one signal dominated."""
-    if step_path == "fused":
-        pytest.skip("the mean gradient of this configuration does not fit on chip: same path as three_kernel")
+    """d = 351M, S = 64: 45 GB of bf16 gradients resident; the oracle (OpenMP build) checks the two
+    ends of the signal-to-noise sweep: iteration 0 (signal dominated, gain near 1) and iteration 49
+    (noise dominated, one-sample gain near 60)."""
     wl = W.config(5)
     inp = W.Inputs(wl, "cuda:0")
-    rep = H.run_teacher_forced(wl, n_steps=2, check_steps=[0, 1], openmp=True, inputs=inp, log=log)
+    rep = H.run_teacher_forced(wl, step_ids=[0, 49], openmp=True, inputs=inp, log=log)
     H.assert_report(rep)
+    assert rep.steps[0].r < 1.2 and rep.steps[1].r > rep.steps[0].r
