@@ -149,6 +149,13 @@ def main() -> int:
         cpu = {"value": round(grad_bytes / csec / 1e9, 3), "unit": "GB/s", "cores": orc.threads, "kind": "oracle",
                "sample": f"{reps} full step(s) of the same workload ({S * d / 1e6:.0f}M gradient elements each), "
                          f"OpenMP build of the oracle source, {csec:.3f} s/step"}
+        if S * d <= 1 << 30:                          # the single-threaded build as well, one step
+            one = H.make_oracle(wl, openmp=False)
+            c0 = time.perf_counter()
+            one.step(w64, v64, g_np)
+            c1 = time.perf_counter() - c0
+            cpu["single_thread"] = {"value": round(grad_bytes / c1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                                    "sample": f"1 full step, {c1:.3f} s"}
 
     out = {
         "metric": "adascale_step gradient GB/s (S*d*b / step time), 1 GPU",

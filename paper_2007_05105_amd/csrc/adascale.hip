@@ -1256,8 +1256,10 @@ const void *fused_kernel_for(int dtype, int S, int level, bool lag, int *regs = 
     }
 }
 
-// Decide whether the fused single-launch step applies and build its tile tables.  It needs fp32
-// gradients, S <= 16, and enough of the mean gradient to fit on chip to be worth it.
+// Decide whether the fused single-launch step applies and build its tile tables: whole tiles
+// (inside one tensor) and the ragged last tile of each tensor, the grid (one workgroup per CU),
+// tiles per workgroup, the LDS capacity in tiles and the register-slot level.  Which instance
+// runs is looked up per step from the scale of the moment (it may change between steps).
 int setup_fused(adascale_ctx *c)
 {
     c->fused_ok = false;

@@ -4,6 +4,7 @@ sigma2_hat, mu2_hat (against max(|value|, 1e-4 A/S)), r and tau; |dw| <= 1e-6 ma
 The same 1e-6 bar is applied to bf16-gradient runs (the definition allows 1e-2 there) and to v.
 """
 import ctypes as C
+import math
 
 import numpy as np
 import pytest
@@ -229,6 +230,50 @@ def test_elastic_scale_and_checkpoint_resume():
     assert st2.tau == final[0].tau and st2.r == final[0].r and st2.step == final[0].step
     assert torch.equal(w_flat2, final[1])
     g2.close()
+
+
+@pytest.mark.parametrize("scales", [(32, 64, 128), (128, 64, 32)], ids=["growing", "shrinking"])
+def test_elastic_scale_changes_at_quarter_and_half_of_the_budget(scales, step_path):
+    """Elastic AdaScaling as the paper runs it (Sec. 4): the scale doubles (or halves) when tau
+    passes T_SI/4 and T_SI/2, theta follows the scale (max(1 - S/1000, 0)), and the run ends at
+    tau >= T_SI.  bf16 gradients over several tensors; S = 128 has no fused instance, so the run
+    also crosses from one step path to the other.  The oracle runs freely beside the GPU."""
+    shapes = [(300, 1000), (4099,), (2048 * 3,), (17, 31)]
+    L = 600
+    wls = {S: W.custom(shapes, S, grad_dtype=BF16, theta=-1.0, weight_decay=1e-4,
+                       lr_table=W.lr_step_decay(0.05, L), steps=30, seed=21)
+           for S in scales}
+    inp = {S: W.Inputs(wls[S], "cuda:0") for S in scales}
+    first = inp[scales[0]]
+    w = W.views(first.w_flat, first.wl.numel, first.offs32)
+    v = W.views(first.v_flat, first.wl.numel, first.offs32)
+    w64 = [x.cpu().numpy().astype(np.float64) for x in w]
+    v64 = [x.cpu().numpy().astype(np.float64) for x in v]
+    w0 = [x.copy() for x in w64]
+    gpu = H.make_gpu(wls[scales[0]])
+    orc = H.make_oracle(wls[scales[0]])
+    tau, t, seen = 0.0, 0, []
+    while tau < L:
+        assert t < 60, "the run should reach tau >= T_SI within a few dozen iterations"
+        S = scales[0] if tau < L / 4 else scales[1] if tau < L / 2 else scales[2]
+        if gpu.S != S:
+            gpu.set_scale(S, -1.0)
+            orc.set_scale(S, -1.0)
+        inp[S].fill_grads(t)
+        gpu.step(w, v, inp[S].g)
+        ost = orc.step(w64, v64, H.grads_to_numpy(inp[S]))
+        gst = gpu.get_state()
+        rel = H.compare_step(gst, ost, S)
+        assert max(rel[k] for k in ("sigma2_hat", "mu2_hat", "r", "tau", "lr_eff")) <= H.TOL_SCALAR, (t, S, rel)
+        assert 1.0 <= gst.r <= S * (1 + 1e-12)
+        tau, t = gst.tau, t + 1
+        seen.append(S)
+    assert gst.done == 1 and ost.done == 1
+    assert list(dict.fromkeys(seen)) == list(scales)          # all three scales were visited, in order
+    assert math.ceil(L / max(scales)) <= t <= L               # iteration bounds of Sec. 3.2
+    # free-running drift of w over the whole run (fp32 storage against the fp64 oracle)
+    assert H.tensor_err(first.w_flat, w64, w0, first.wl.numel, first.offs32) <= 2e-5
+    gpu.close()
 
 
 def test_error_paths_launch_nothing():
