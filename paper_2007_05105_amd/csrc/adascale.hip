@@ -19,6 +19,7 @@
 // the span, so the reduction result does not depend on scheduling.
 
 #include <hip/hip_runtime.h>
+#include <type_traits>
 
 #include <algorithm>
 #include <cmath>
@@ -93,13 +94,17 @@ __device__ __forceinline__ void load_f32(const float *p, float (&x)[VEC])
         x[4 * q] = t.x; x[4 * q + 1] = t.y; x[4 * q + 2] = t.z; x[4 * q + 3] = t.w;
     }
 }
-template <int VEC>
+// STREAM: streaming store, for the mean gradient on its way to the HBM scratch (measured: the
+// gradient sweep that writes it runs 4-11 % faster than with plain stores, which linger in L2
+// and leave it in no particular order).
+template <int VEC, bool STREAM = false>
 __device__ __forceinline__ void store_f32(float *p, const float (&x)[VEC])
 {
 #pragma unroll
     for (int q = 0; q < VEC / 4; ++q) {
         f4 t = {x[4 * q], x[4 * q + 1], x[4 * q + 2], x[4 * q + 3]};
-        *(gp_f4)(p + 4 * q) = t;
+        if constexpr (STREAM) __builtin_nontemporal_store(t, (gp_f4)(p + 4 * q));
+        else *(gp_f4)(p + 4 * q) = t;
     }
 }
 
@@ -272,12 +277,11 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
                                                      const long long *__restrict__ numel,
                                                      const unsigned long long *__restrict__ ptrs,
                                                      double *__restrict__ partials, int n_tiles, int span_tiles,
-                                                     int n_spans, int S, double inv_S)
+                                                     int n_spans, int S, int row_len, double inv_S)
 {
     constexpr int VEC = Traits<GT>::VEC;
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
-    const int row_len = S + kRowG;
     __shared__ double sh[kWaves][2];
 
     for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
@@ -295,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce(const int *__restrict__ spa
             if (rem >= VEC) {
                 float out[VEC];
                 reduce_lane_full<GT, HG>(row, base, S, inv_S, out, acc_a, acc_b);
-                store_f32<VEC>(gbar, out);
+                store_f32<VEC, true>(gbar, out);
             } else {
                 for (int e = 0; e < (int)rem; ++e) gbar[e] = reduce_element<GT>(row, base + e, S, inv_S, acc_a, acc_b);
             }
@@ -438,13 +442,12 @@ __global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restric
                                                             double *__restrict__ partials,
                                                             const DevState *__restrict__ st,
                                                             const float *__restrict__ lr, ScalarArgs sc, int n_tiles,
-                                                            int span_tiles, int n_spans, int S, double inv_S, float rho,
-                                                            float lambda)
+                                                            int span_tiles, int n_spans, int S, int row_len,
+                                                            double inv_S, float rho, float lambda)
 {
     constexpr int VEC = Traits<GT>::VEC;
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
-    const int row_len = S + kRowG;
     __shared__ double sh[kWaves][2];
     const float eta = lagged_eta(st, lr, sc);
 
@@ -667,18 +670,18 @@ struct FGrad<Bf16> {
 // A tile's S = HG * NH replicas are consumed in NH (even) half-groups of HG replicas, alternating
 // between two register buffers: while one half-group is accumulated, the loads of the next one
 // (of the same tile, or of the next tile after the last half-group) are in flight.
-// MASK: S may be smaller than HG * NH; replica slots at or past S re-read the last replica (no
-// branch, the line is already on its way) and count as zero when accumulated.
+// MASK: S may be smaller than HG * NH; the host pads every pointer row to HG * NH replica slots
+// by repeating the last replica, so slots at or past S re-read it (no branch, no index clamp:
+// the pointers of a half-group are adjacent in the row and come with one scalar load) and count
+// as zero when accumulated.
 template <typename GT, int HG, bool MASK>
-__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, int S,
+__device__ __forceinline__ void fused_issue(const FLoc &L, unsigned lane_off, int first, int /*S*/,
                                             typename FGrad<GT>::raw (&x)[HG])
 {
 #pragma unroll
-    for (int g = 0; g < HG; ++g) {
-        const int i = MASK ? min(first + g, S - 1) : first + g;
-        x[g] = FGrad<GT>::load((gp_cchar)(L.row[kRowG + i] + (L.tile_off >> FGrad<GT>::kShift)) +
+    for (int g = 0; g < HG; ++g)
+        x[g] = FGrad<GT>::load((gp_cchar)(L.row[kRowG + first + g] + (L.tile_off >> FGrad<GT>::kShift)) +
                                (lane_off >> FGrad<GT>::kShift));
-    }
 }
 
 template <typename GT, int HG, bool MASK>
@@ -694,12 +697,28 @@ __device__ __forceinline__ void fused_accumulate(const typename FGrad<GT>::raw (
     acc.flush();
 }
 
+// Workgroup barrier that publishes this wave's LDS writes; global loads stay in flight.
+__device__ __forceinline__ void lds_release_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+struct NoHook {
+    __device__ __forceinline__ void operator()() const {}
+};
+
 // Mean gradient of one full tile plus its contribution to A and B.  On entry `xa` holds (in
 // flight) half-group 0 of this tile; on return half-group 0 of the NEXT tile is in flight there
 // (the last tile of a workgroup names itself as next: a few redundant loads, no branch).
-template <typename GT, int HG, int NH, bool MASK>
+// `hook` runs once, right after the second half-group has been issued: work with long latencies
+// of its own (cross-lane sums) hides there behind loads that have to be waited for anyway; LDS
+// writes it makes are published by the barrier at the end.
+template <typename GT, int HG, int NH, bool MASK, typename HOOK = NoHook>
 __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, int S, double inv_S,
-                                              typename FGrad<GT>::raw (&xa)[HG], double &acc_a, double &acc_b)
+                                              typename FGrad<GT>::raw (&xa)[HG], double &acc_a, double &acc_b,
+                                              const HOOK &hook = HOOK())
 {
     static_assert(NH % 2 == 0, "half-groups alternate between two buffers");
     typename FGrad<GT>::Acc acc;
@@ -711,6 +730,10 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     for (int h = 0; h < NH; h += 2) {
         fused_issue<GT, HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (!std::is_same<HOOK, NoHook>::value) {
+            if (h == 0) hook();
+            __builtin_amdgcn_sched_barrier(0);
+        }
         fused_accumulate<GT, HG, MASK>(xa, h * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
         if (h + 2 < NH) fused_issue<GT, HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
@@ -731,7 +754,8 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     acc_b += b;
     // Keep the 8 waves of the workgroup on the same tile: left alone, the older waves win the
     // arbitration for the memory pipeline and the workgroup then waits for its youngest wave.
-    __builtin_amdgcn_s_barrier();
+    if constexpr (std::is_same<HOOK, NoHook>::value) __builtin_amdgcn_s_barrier();
+    else lds_release_barrier();
     return f4{o[0], o[1], o[2], o[3]};
 }
 
@@ -765,7 +789,7 @@ struct FusedArgs {
     unsigned long long *barrier;   // monotonically increasing arrival counter
     unsigned long long barrier_target;
     int *fault;                    // set when the bounded wait at the barrier gave up
-    int n_tiles, n_cold, tiles_per_block, lds_tiles, S;
+    int n_tiles, n_cold, tiles_per_block, lds_tiles, S, row_len;
     double inv_S;
     float rho, lambda;
     ScalarArgs sc;
@@ -786,12 +810,12 @@ struct FusedArgs {
 // Ragged last tile of a tensor, phase 1: per-lane predicates, mean gradient to the HBM scratch.
 // Lanes wholly inside the tensor use one 16-byte load per replica, the lane on the boundary
 // single elements; the replicas are loaded HG at a time so that their latencies overlap.
-template <typename GT, int HG>
-__device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int tid, double &acc_a, double &acc_b)
+template <typename GT, int HG, typename ARGS>
+__device__ __forceinline__ void fused_cold_mean(const ARGS &p, int c, int tid, double &acc_a, double &acc_b)
 {
     const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
     const int k = tp[0], local = tp[1];
-    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * (p.S + kRowG);
+    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * p.row_len;
     const long long first = (long long)local * kFTile + (long long)tid * 4;
     const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
     if (rem <= 0) return;
@@ -802,7 +826,7 @@ __device__ __forceinline__ void fused_cold_mean(const FusedArgs &p, int c, int t
         typename FGrad<GT>::raw x[HG];
 #pragma unroll
         for (int g = 0; g < HG; ++g) {
-            gp_cchar gp = (gp_cchar)row[kRowG + min(i0 + g, p.S - 1)] + ((first * 4) >> FGrad<GT>::kShift);
+            gp_cchar gp = (gp_cchar)row[kRowG + i0 + g] + ((first * 4) >> FGrad<GT>::kShift);
             x[g] = c4 == 4 ? FGrad<GT>::load(gp) : FGrad<GT>::load_partial(gp, c4);
         }
         fused_accumulate<GT, HG, true>(x, i0, p.S, acc);
@@ -831,7 +855,7 @@ __device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int
 {
     const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
     const int k = tp[0], local = tp[1];
-    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * (p.S + kRowG);
+    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * p.row_len;
     const long long first = (long long)local * kFTile + (long long)tid * 4;
     const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
     if (rem <= 0) return;
@@ -927,7 +951,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     const int n_valid = b < p.n_tiles ? (p.n_tiles - 1 - b) / G + 1 : 0;
     const int q_hbm = min(R + p.lds_tiles, p.tiles_per_block);
     const int q_lds_end = min(q_hbm, n_valid);
-    const FCtx<R> cx{p, b, G, p.S + kRowG, q_hbm, n_valid};
+    const FCtx<R> cx{p, b, G, p.row_len, q_hbm, n_valid};
     const unsigned lane_off = (unsigned)tid * 16u;
 
     f4 keep[R > 0 ? R : 1];
@@ -935,7 +959,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 
     // phase 1
     FUSED_STAMP(0);
-    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG>(p, c, tid, acc_a, acc_b);
+    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, FusedArgs>(p, c, tid, acc_a, acc_b);
     FUSED_STAMP(1);
 
     if (n_valid > 0) {
@@ -946,7 +970,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         for (int q = q_hbm; q < n_valid; ++q) {
             const FLoc next = cx.locate(cx.after(q));
             const f4 m = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
-            *(gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off) = m;
+            __builtin_nontemporal_store(m, (gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off));
             cur = next;
         }
         for (int q = R; q < q_lds_end; ++q) {
@@ -1047,6 +1071,142 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     FUSED_STAMP(4);
 }
 
+// ---------------------------------------------------------------------------------------------
+// streaming reduce: the first kernel of the three-kernel step for parameter lists far larger
+// than the chip (the fused step then keeps little of the mean gradient on chip).
+//
+// Measured on this memory system: a gradient sweep that also writes the mean gradient reads at
+// ~5.1 TB/s instead of ~6.9 TB/s, however small the write stream is -- unless the accesses of
+// the whole chip stay close together in memory and the writes bypass the cache: one persistent
+// workgroup per CU, tiles handed out in memory order from one global counter (the front is then
+// 256 tiles wide), streaming stores.  That reads at ~6.1 TB/s.
+//
+// Unit of work: a pair of consecutive full tiles (512 lanes x 4 elements each).  A workgroup
+// claims pairs two ahead (the counter's latency is hidden behind a pair of tiles), the first
+// half-group of a tile is in flight before the previous tile ends, and each pair leaves its
+// contribution to A and B in the pair's own slot, so the sums do not depend on which workgroup
+// took which pair: k_scalars adds the slots in index order.  The ragged last tiles of the
+// tensors are shared out statically; their contribution goes to the workgroup's slot.
+struct StreamArgs {
+    const FTile *tiles;            // full tiles   } read through the constant address space
+    const FTile *cold;             // ragged tiles }
+    const long long *numel;
+    const unsigned long long *ptrs;
+    double *partials;              // [gridDim.x + pairs][2]
+    unsigned *claim;               // pairs handed out so far in this launch (zero on entry)
+    unsigned *claim_next;          // the next launch's counter: zeroed here
+    int n_tiles, n_cold, S, row_len;
+    double inv_S;
+};
+
+template <typename GT, int HG, int NH, bool MASK>
+__global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
+{
+    __shared__ double red[1][kFWaves][2];
+    __shared__ int s_claim[2];
+    const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
+    const unsigned lane_off = (unsigned)tid * 16u;
+    const int row_len = p.row_len;
+    const int n_pairs = (p.n_tiles + 1) >> 1;
+
+    auto claim = [&]() -> int {
+        const unsigned c = __hip_atomic_fetch_add(p.claim, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return c < (unsigned)n_pairs ? (int)c : -1;
+    };
+    int pend = -1;  // lane 0: the pair after the next one
+    if (tid == 0) {
+        if (b == 0) *p.claim_next = 0u;
+        s_claim[0] = claim();
+        s_claim[1] = claim();
+        pend = claim();
+    }
+
+    // ragged tiles -> this workgroup's slot
+    {
+        double acc_a = 0.0, acc_b = 0.0;
+        for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, StreamArgs>(p, c, tid, acc_a, acc_b);
+        acc_a = wave_sum(acc_a);
+        acc_b = wave_sum(acc_b);
+        if ((tid & (kWave - 1)) == 0) {
+            red[0][tid >> 6][0] = acc_a;
+            red[0][tid >> 6][1] = acc_b;
+        }
+        __syncthreads();
+        if (tid < 2) {
+            double t = red[0][0][tid];
+#pragma unroll
+            for (int w = 1; w < kFWaves; ++w) t += red[0][w][tid];
+            p.partials[(size_t)b * 2 + tid] = t;
+        }
+        __syncthreads();
+    }
+
+    auto locate = [&](int t) -> FLoc {
+        const AS_CONST int *tp = (const AS_CONST int *)p.tiles + 2 * (size_t)t;
+        return FLoc{(cp_u64)p.ptrs + (size_t)tp[0] * row_len, (unsigned long long)tp[1] * (kFTile * 4ULL)};
+    };
+    auto store_mean = [&](const FLoc &L, f4 m) {
+        __builtin_nontemporal_store(m, (gp_f4)((gp_char)(L.row[kRowGbar] + L.tile_off) + lane_off));
+    };
+    auto finish = [&](int pair) {  // after a barrier: the pair's contribution in wave order
+        if (tid < 2) {
+            double t = red[0][0][tid];
+#pragma unroll
+            for (int w = 1; w < kFWaves; ++w) t += red[0][w][tid];
+            p.partials[((size_t)G + pair) * 2 + tid] = t;
+        }
+    };
+
+    int cur = __builtin_amdgcn_readfirstlane(s_claim[0]);
+    int nxt = __builtin_amdgcn_readfirstlane(s_claim[1]);
+    if (cur < 0) return;
+    int par = 0, prev = -1;
+    double prev_a = 0.0, prev_b = 0.0;  // this lane's contributions of the previous pair
+    // The cross-lane sum of a pair's contributions is a chain of long-latency lane exchanges: it
+    // runs inside the next pair's first tile, behind that tile's loads.
+    auto wave_partials = [&]() {
+        if (prev >= 0) {
+            const double a = wave_sum(prev_a), bsum = wave_sum(prev_b);
+            if ((tid & (kWave - 1)) == 0) {
+                red[0][tid >> 6][0] = a;
+                red[0][tid >> 6][1] = bsum;
+            }
+        }
+    };
+    typename FGrad<GT>::raw xa[HG];
+    FLoc L0 = locate(2 * cur);
+    fused_issue<GT, HG, MASK>(L0, lane_off, 0, p.S, xa);
+    while (cur >= 0) {
+        const bool two = 2 * cur + 1 < p.n_tiles;
+        const FLoc L1 = locate(two ? 2 * cur + 1 : 2 * cur);
+        const FLoc LN = locate(nxt >= 0 ? 2 * nxt : 2 * cur);  // at the end: a few redundant loads, no branch
+        double acc_a = 0.0, acc_b = 0.0;
+        f4 m = fused_tile_mean<GT, HG, NH, MASK>(L0, two ? L1 : LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b,
+                                                 wave_partials);
+        store_mean(L0, m);
+        if (prev >= 0) finish(prev);
+        if (two) {
+            m = fused_tile_mean<GT, HG, NH, MASK>(L1, LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+            store_mean(L1, m);
+        }
+        prev_a = acc_a;
+        prev_b = acc_b;
+        if (tid == 0) {
+            s_claim[par] = pend;
+            pend = pend >= 0 ? claim() : -1;
+        }
+        lds_release_barrier();  // the claim is published; the reads of `red` above are done
+        prev = cur;
+        cur = nxt;
+        nxt = __builtin_amdgcn_readfirstlane(s_claim[par]);
+        par ^= 1;
+        L0 = LN;
+    }
+    wave_partials();
+    lds_release_barrier();
+    finish(prev);
+}
+
 __global__ void k_set_state(DevState *st, long long step, double tau, double sbar, double mbar, long long L)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -1083,7 +1243,7 @@ struct adascale_ctx {
     int vec = 4, tile = 1024;
     int n_tiles = 0, span_tiles = 2, n_spans = 0, max_blocks = 1 << 30, group = 0;
     int update_reverse = 0;
-    int S_cap = 0;                  // pointer table capacity in replicas
+    int S_cap = 0;                  // pointer table capacity in replica slots per row
 
     int *d_span_first = nullptr, *d_tile_prefix = nullptr;
     long long *d_numel = nullptr;
@@ -1101,6 +1261,12 @@ struct adascale_ctx {
     unsigned long long fused_launches = 0;
     int f_grid = 0, f_tpb = 0, f_lds_cap = 0, f_level = 0;
     bool fused_ok = false;
+
+    // streaming reduce (first kernel of the three-kernel step)
+    bool tiles_ok = false, stream_ok = false;
+    int n_cus = 0, s_grid = 0;
+    unsigned *d_claim = nullptr;         // two counters: a launch uses one and zeroes the other
+    unsigned long long stream_launches = 0;
 
     DevState *h_state = nullptr;    // pinned
     unsigned long long *h_ring[kRing] = {};
@@ -1143,11 +1309,18 @@ int env_int(const char *name, int dflt)
     return v > 0 ? (int)v : dflt;
 }
 
-size_t table_len(const adascale_ctx *c, int S) { return (size_t)c->numel.size() * (size_t)(S + kRowG); }
+// Replica slots in a pointer-table row: the 512-lane kernels read whole half-groups, so rows are
+// padded to their HG * NH slots (the padding repeats the last replica).
+int padded_scale(int dtype, int S);
+size_t table_len(const adascale_ctx *c, int S)
+{
+    return (size_t)c->numel.size() * (size_t)(padded_scale(c->cfg.grad_dtype, S) + kRowG);
+}
 
 int alloc_pointer_tables(adascale_ctx *c, int S)
 {
-    if (S <= c->S_cap) return ADASCALE_OK;
+    const int slots = padded_scale(c->cfg.grad_dtype, S);
+    if (slots <= c->S_cap) return ADASCALE_OK;
     const size_t bytes = std::max<size_t>(table_len(c, S), 1) * sizeof(unsigned long long);
     if (c->d_ptrs) {
         HIP_TRY(c, hipDeviceSynchronize());
@@ -1161,7 +1334,7 @@ int alloc_pointer_tables(adascale_ctx *c, int S)
     }
     HIP_TRY(c, hipMalloc(&c->d_ptrs, bytes));
     for (int i = 0; i < kRing; ++i) HIP_TRY(c, hipHostMalloc(&c->h_ring[i], bytes, hipHostMallocDefault));
-    c->S_cap = S;
+    c->S_cap = slots;
     c->table_valid = false;
     return ADASCALE_OK;
 }
@@ -1212,6 +1385,12 @@ bool fused_shape(int dtype, int S, int *hg, int *nh)
     return true;
 }
 
+int padded_scale(int dtype, int S)
+{
+    int hg = 0, nh = 0;
+    return fused_shape(dtype, S, &hg, &nh) ? hg * nh : S;
+}
+
 template <int LEVEL, bool LAG>
 const void *fused_kernel_at(int dtype, int S)
 {
@@ -1256,18 +1435,49 @@ const void *fused_kernel_for(int dtype, int S, int level, bool lag, int *regs = 
     }
 }
 
-// Decide whether the fused single-launch step applies and build its tile tables: whole tiles
-// (inside one tensor) and the ragged last tile of each tensor, the grid (one workgroup per CU),
-// tiles per workgroup, the LDS capacity in tiles and the register-slot level.  Which instance
-// runs is looked up per step from the scale of the moment (it may change between steps).
-int setup_fused(adascale_ctx *c)
+// The streaming reduce kernel instance for a gradient type and scale (nullptr: none).
+const void *stream_kernel_for(int dtype, int S)
 {
-    c->fused_ok = false;
-    if (env_int("ADASCALE_FUSED", 1) == 2) return ADASCALE_OK;              // 2 = force the three-kernel step
+#define KS(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_reduce_stream<GT, HG, NH, MASK>)
+    int hg = 0, nh = 0;
+    if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
+    const bool exact = hg * nh == S;
+    if (dtype == ADASCALE_F32) {
+        switch (hg * 100 + nh) {
+        case 102: return exact ? KS(float, 1, 2, false) : KS(float, 1, 2, true);
+        case 202: return exact ? KS(float, 2, 2, false) : KS(float, 2, 2, true);
+        case 402: return exact ? KS(float, 4, 2, false) : KS(float, 4, 2, true);
+        case 404: return exact ? KS(float, 4, 4, false) : KS(float, 4, 4, true);
+        case 408: return KS(float, 4, 8, true);
+        default: return nullptr;
+        }
+    }
+    switch (hg * 100 + nh) {
+    case 102: return KS(Bf16, 1, 2, true);
+    case 202: return KS(Bf16, 2, 2, true);
+    case 402: return KS(Bf16, 4, 2, true);
+    case 802: return KS(Bf16, 8, 2, true);
+    case 804: return KS(Bf16, 8, 4, true);
+    case 808: return KS(Bf16, 8, 8, true);
+    default: return nullptr;
+    }
+#undef KS
+}
+
+// Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
+// so that its workgroups (one per CU in number) also land one per CU.
+constexpr size_t kStreamLdsPad = 96 * 1024;
+constexpr int kFusedMinPct = 25;  // least share of the mean gradient on chip for the fused step
+
+// Tile tables of the 512-lane kernels: whole tiles (inside one tensor) and the ragged last tile
+// of each tensor; the streaming reduce kernel's grid and counters.
+int setup_tiles(adascale_ctx *c)
+{
+    c->tiles_ok = c->stream_ok = false;
     if (c->d == 0) return ADASCALE_OK;
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
-    if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
+    c->n_cus = prop.multiProcessorCount;
     const int N = (int)c->numel.size();
     c->ftiles.clear();
     c->ctiles.clear();
@@ -1278,6 +1488,40 @@ int setup_fused(adascale_ctx *c)
         for (long long j = 0; j < nf; ++j) c->ftiles.push_back(FTile{k, (int)j});
         if (c->numel[k] % kFTile) c->ctiles.push_back(FTile{k, (int)nf});
     }
+    const size_t nt = c->ftiles.size(), nc = c->ctiles.size();
+    HIP_TRY(c, hipMalloc(&c->d_ftiles, sizeof(FTile) * std::max<size_t>(nt, 1)));
+    HIP_TRY(c, hipMalloc(&c->d_ctiles, sizeof(FTile) * std::max<size_t>(nc, 1)));
+    if (nt) HIP_TRY(c, hipMemcpy(c->d_ftiles, c->ftiles.data(), sizeof(FTile) * nt, hipMemcpyHostToDevice));
+    if (nc) HIP_TRY(c, hipMemcpy(c->d_ctiles, c->ctiles.data(), sizeof(FTile) * nc, hipMemcpyHostToDevice));
+    c->tiles_ok = true;
+
+    if (env_int("ADASCALE_STREAM", 1) == 2) return ADASCALE_OK;  // 2 = keep to the plain reduce kernel
+    if (prop.sharedMemPerBlock < kStreamLdsPad + 1024) return ADASCALE_OK;
+    const long long n_pairs = ((long long)nt + 1) / 2;
+    c->s_grid = (int)std::max<long long>(1, std::min<long long>(std::max<long long>(n_pairs, (long long)nc),
+                                                               std::min(c->n_cus, kFMaxGrid)));
+    const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
+    for (int S = 1; S <= max_scale; ++S) {
+        const void *fn = stream_kernel_for(c->cfg.grad_dtype, S);
+        if (fn) HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsPad));
+    }
+    HIP_TRY(c, hipMalloc(&c->d_claim, 2 * sizeof(unsigned)));
+    HIP_TRY(c, hipMemset(c->d_claim, 0, 2 * sizeof(unsigned)));
+    c->stream_ok = true;
+    return ADASCALE_OK;
+}
+
+// Decide whether the fused single-launch step applies: the grid (one workgroup per CU), tiles
+// per workgroup, the LDS capacity in tiles and the register-slot level.  Which instance runs is
+// looked up per step from the scale of the moment (it may change between steps).
+int setup_fused(adascale_ctx *c)
+{
+    c->fused_ok = false;
+    if (env_int("ADASCALE_FUSED", 1) == 2) return ADASCALE_OK;              // 2 = force the three-kernel step
+    if (!c->tiles_ok) return ADASCALE_OK;
+    hipDeviceProp_t prop;
+    HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
+    if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
     const long long nt = (long long)c->ftiles.size(), nc = (long long)c->ctiles.size();
     const int cus = std::min(std::min(prop.multiProcessorCount, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
     const int grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
@@ -1286,10 +1530,10 @@ int setup_fused(adascale_ctx *c)
     for (int l = 0; l < kFRegLevels; ++l)
         if (fused_regs_at(l, 2) <= nt / grid) level = l;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
-    // the fused step pays as soon as part of the mean gradient stays on chip (12 % faster with
-    // half of it there, 3 % with a tenth); the percentage is a development knob
+    // with little of the mean gradient on chip the three-kernel step with the streaming reduce
+    // kernel is the faster one (measured: equal at ~40 % on chip, 10 % ahead at 6 %)
     const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level, 2) + std::min(tpb, lds_cap)) / tpb);
-    if (on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", 0)) return ADASCALE_OK;
+    if (c->stream_ok && on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
     const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
     for (int S = 1; S <= max_scale; ++S) {
@@ -1300,10 +1544,6 @@ int setup_fused(adascale_ctx *c)
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
         if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < grid) return ADASCALE_OK;
     }
-    HIP_TRY(c, hipMalloc(&c->d_ftiles, sizeof(FTile) * std::max<size_t>(c->ftiles.size(), 1)));
-    HIP_TRY(c, hipMalloc(&c->d_ctiles, sizeof(FTile) * std::max<size_t>(c->ctiles.size(), 1)));
-    if (nt) HIP_TRY(c, hipMemcpy(c->d_ftiles, c->ftiles.data(), sizeof(FTile) * nt, hipMemcpyHostToDevice));
-    if (nc) HIP_TRY(c, hipMemcpy(c->d_ctiles, c->ctiles.data(), sizeof(FTile) * nc, hipMemcpyHostToDevice));
     c->f_grid = grid;
     c->f_tpb = tpb;
     c->f_lds_cap = lds_cap;
@@ -1316,10 +1556,11 @@ template <typename GT>
 void launch_reduce(const adascale_ctx *c, int grid, hipStream_t s, int S)
 {
     const double inv_S = 1.0 / (double)S;
+    const int row_len = padded_scale(c->cfg.grad_dtype, S) + kRowG;
 #define LAUNCH(HH)                                                                                   \
     hipLaunchKernelGGL((k_reduce<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,        \
                        c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, c->n_tiles,           \
-                       c->span_tiles, c->n_spans, S, inv_S)
+                       c->span_tiles, c->n_spans, S, row_len, inv_S)
     const int H = c->group > 0 ? c->group : 8;  // replicas per half-group (two half-groups in flight)
     if (S >= 16 && H >= 8) LAUNCH(8);
     else if (S >= 8 && H >= 4) LAUNCH(4);
@@ -1332,11 +1573,12 @@ template <typename GT>
 void launch_reduce_update(const adascale_ctx *c, int grid, hipStream_t s, int S, const DevState *st, const ScalarArgs &sa)
 {
     const double inv_S = 1.0 / (double)S;
+    const int row_len = padded_scale(c->cfg.grad_dtype, S) + kRowG;
     const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
 #define LAUNCH(HH)                                                                                         \
     hipLaunchKernelGGL((k_reduce_update<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,       \
                        c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, st, c->d_lr, sa, c->n_tiles, \
-                       c->span_tiles, c->n_spans, S, inv_S, rho, lambda)
+                       c->span_tiles, c->n_spans, S, row_len, inv_S, rho, lambda)
     const int H = c->group > 0 ? c->group : 8;
     if (S >= 16 && H >= 8) LAUNCH(8);
     else if (S >= 8 && H >= 4) LAUNCH(4);
@@ -1431,7 +1673,10 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         HIP_TRY(c, hipMalloc(&c->d_numel, sizeof(long long) * std::max(N, 1)));
         HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * std::max<size_t>(goff, 64)));
         HIP_TRY(c, hipMalloc(&c->d_lr, sizeof(float) * cfg->lr_table_len));
-        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * std::max(c->n_spans, kFMaxGrid)));
+        // partial slots: one per span (reduce kernel), per workgroup (fused step), or per workgroup
+        // plus one per pair of 512-lane tiles (streaming reduce kernel)
+        const size_t n_slots = std::max<size_t>((size_t)c->n_spans, (size_t)kFMaxGrid + (size_t)(c->d / (2 * kFTile)) + 1);
+        HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * n_slots));
         HIP_TRY(c, hipMalloc(&c->d_state, 2 * sizeof(DevState)));
         HIP_TRY(c, hipMalloc(&c->d_fault, sizeof(int)));
         HIP_TRY(c, hipMalloc(&c->d_barrier, sizeof(unsigned long long)));
@@ -1446,7 +1691,9 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
             HIP_TRY(c, hipMemcpy(c->d_numel, c->numel.data(), sizeof(long long) * N, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_lr, cfg->lr_table, sizeof(float) * cfg->lr_table_len, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemset(c->d_state, 0, 2 * sizeof(DevState)));
-        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * std::max(c->n_spans, kFMaxGrid)));
+        HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * n_slots));
+        const int trc = setup_tiles(c);
+        if (trc != ADASCALE_OK) return trc;
         const int frc = setup_fused(c);
         if (frc != ADASCALE_OK) return frc;
         return alloc_pointer_tables(c, cfg->S);
@@ -1478,6 +1725,7 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_barrier);
     (void)hipFree(c->d_ftiles);
     (void)hipFree(c->d_ctiles);
+    (void)hipFree(c->d_claim);
     if (c->h_state) (void)hipHostFree(c->h_state);
     for (int i = 0; i < kRing; ++i) {
         if (c->h_ring[i]) (void)hipHostFree(c->h_ring[i]);
@@ -1549,7 +1797,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     HIP_TRY(c, hipSetDevice(c->cfg.device));
 
     // Build the device pointer table [N][3 + S] in a pinned slot; upload only when it changed.
-    const int row_len = S + kRowG;
+    const int S_pad = padded_scale(c->cfg.grad_dtype, S);
+    const int row_len = S_pad + kRowG;
     const size_t len = table_len(c, S);
     if (len > 0) {
         int slot = c->ring_next;
@@ -1560,7 +1809,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             row[kRowW] = (unsigned long long)(uintptr_t)w[k];
             row[kRowV] = (unsigned long long)(uintptr_t)mom[k];
             row[kRowGbar] = (unsigned long long)(uintptr_t)(c->d_gbar + c->gbar_off[k]);
-            for (int i = 0; i < S; ++i) row[kRowG + i] = (unsigned long long)(uintptr_t)grads[(size_t)i * N + k];
+            for (int i = 0; i < S_pad; ++i)
+                row[kRowG + i] = (unsigned long long)(uintptr_t)grads[(size_t)std::min(i, S - 1) * N + k];
         }
         const bool same = c->table_valid && c->last_table.size() == len &&
                           memcmp(c->last_table.data(), tab, len * sizeof(unsigned long long)) == 0;
@@ -1618,6 +1868,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.tiles_per_block = c->f_tpb;
         fa.lds_tiles = f_lds_tiles;
         fa.S = S;
+        fa.row_len = row_len;
         fa.inv_S = 1.0 / (double)S;
         fa.rho = (float)c->cfg.momentum;
         fa.lambda = (float)c->cfg.weight_decay;
@@ -1696,13 +1947,33 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
         return ADASCALE_OK;
     }
-    if (grid > 0) {
+    const void *stream_fn = c->stream_ok ? stream_kernel_for(c->cfg.grad_dtype, S) : nullptr;
+    int n_partials = c->n_spans;
+    if (stream_fn) {
+        StreamArgs ra{};
+        ra.tiles = c->d_ftiles;
+        ra.cold = c->d_ctiles;
+        ra.numel = c->d_numel;
+        ra.ptrs = c->d_ptrs;
+        ra.partials = c->d_partials;
+        ra.claim = c->d_claim + (c->stream_launches & 1);
+        ra.claim_next = c->d_claim + ((c->stream_launches + 1) & 1);
+        ra.n_tiles = (int)c->ftiles.size();
+        ra.n_cold = (int)c->ctiles.size();
+        ra.S = S;
+        ra.row_len = row_len;
+        ra.inv_S = 1.0 / (double)S;
+        void *args[] = {&ra};
+        HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));
+        c->stream_launches += 1;
+        n_partials = c->s_grid + (ra.n_tiles + 1) / 2;
+    } else if (grid > 0) {
         if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, grid, s, S);
         else launch_reduce<Bf16>(c, grid, s, S);
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans, st_in, st_out,
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, st_in, st_out,
                        c->d_lr, sa);
     HIP_TRY(c, hipGetLastError());
     c->cur ^= 1;

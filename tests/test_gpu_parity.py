@@ -25,9 +25,11 @@ def log(msg):
 @pytest.fixture(autouse=True, params=["fused", "three_kernel"])
 def step_path(request, monkeypatch):
     """Every test runs once per implementation of the step: the fused persistent launch (S <= 32
-    for fp32 gradients, <= 64 for bf16: the mean gradient stays on chip as far as it fits) and the
-    three-kernel step (forced here; also what larger scales get)."""
+    for fp32 gradients, <= 64 for bf16: the mean gradient stays on chip as far as it fits; forced
+    here even where the library would not choose it) and the three-kernel step (forced here; also
+    what larger scales and parameter lists far larger than the chip get)."""
     monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
+    monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
     return request.param
 
 
@@ -310,6 +312,31 @@ def test_error_paths_launch_nothing():
     assert g.step_raw(pw, pv, arr([ok[0].data_ptr(), ok[1].data_ptr()]), stream) == 0
     assert g.get_state().step == 1
     g.close()
+
+
+def test_default_choice_of_step_path(step_path, monkeypatch):
+    """Left alone, the library takes the fused step while a fair share of the mean gradient fits
+    on chip (cfg3 entirely, cfg4 about 40 %) and the three-kernel step with the streaming reduce
+    kernel beyond (cfg5: 6 %)."""
+    if step_path != "fused":
+        pytest.skip("one run is enough")
+    monkeypatch.delenv("ADASCALE_FUSED")
+    monkeypatch.delenv("ADASCALE_FUSED_MIN_PCT")
+    for cfg, fused in ((1, True), (3, True), (4, True), (5, False)):
+        g = H.make_gpu(W.config(cfg))
+        assert g.uses_fused_step() == fused, cfg
+        g.close()
+
+
+@pytest.mark.parametrize("S,dtype", [(1, F32), (3, F32), (16, F32), (32, F32), (2, BF16), (11, BF16), (64, BF16)])
+def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, step_path):
+    """Three-kernel step on a list with thousands of tile pairs (each workgroup claims dozens),
+    an odd number of whole tiles, ragged tails and tensors smaller than a tile."""
+    if step_path != "three_kernel":
+        pytest.skip("three-kernel step only")
+    wl = W.custom([(2048 * 1501 + 3,), (5,), (2048 * 700,), (2047,), (2048 * 302 + 2047,)], S, grad_dtype=dtype,
+                  weight_decay=1e-3, theta=0.5, steps=2, seed=100 + S)
+    H.assert_report(H.run_teacher_forced(wl, log=log))
 
 
 # ------------------------------------------------------------------------- the five configs
