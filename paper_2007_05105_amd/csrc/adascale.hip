@@ -85,12 +85,14 @@ struct Traits<Bf16> {
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(Bf16 x) { return __uint_as_float((unsigned)x.bits << 16); }
 
-template <int VEC>
+template <int VEC, bool STREAM = false>
 __device__ __forceinline__ void load_f32(const float *p, float (&x)[VEC])
 {
 #pragma unroll
     for (int q = 0; q < VEC / 4; ++q) {
-        f4 t = *(gp_cf4)(p + 4 * q);
+        f4 t;
+        if constexpr (STREAM) t = __builtin_nontemporal_load((gp_cf4)(p + 4 * q));
+        else t = *(gp_cf4)(p + 4 * q);
         x[4 * q] = t.x; x[4 * q + 1] = t.y; x[4 * q + 2] = t.z; x[4 * q + 3] = t.w;
     }
 }
@@ -493,7 +495,10 @@ __global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restric
 
 // ---------------------------------------------------------------------------------------------
 // update: momentum-SGD with eta_t taken from device memory.
-template <int VEC>
+// STREAM: streaming loads and stores throughout, for parameter lists far larger than the caches
+// (measured +7 % there; smaller lists profit from finding w and v in the memory-side cache at
+// the next step, which streaming stores prevent).
+template <int VEC, bool STREAM>
 __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ span_first,
                                                      const int *__restrict__ tile_prefix,
                                                      const long long *__restrict__ numel,
@@ -523,17 +528,17 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
             const float *g = reinterpret_cast<const float *>(row[kRowGbar]) + base;
             if (rem >= VEC) {
                 float gv[VEC], wv[VEC], vv[VEC];
-                load_f32<VEC>(g, gv);
-                load_f32<VEC>(w, wv);
-                load_f32<VEC>(v, vv);
+                load_f32<VEC, STREAM>(g, gv);
+                load_f32<VEC, STREAM>(w, wv);
+                load_f32<VEC, STREAM>(v, vv);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
                     const float u = fmaf(lambda, wv[e], gv[e]);
                     vv[e] = fmaf(rho, vv[e], u);
                     wv[e] = fmaf(-eta, vv[e], wv[e]);
                 }
-                store_f32<VEC>(v, vv);
-                store_f32<VEC>(w, wv);
+                store_f32<VEC, STREAM>(v, vv);
+                store_f32<VEC, STREAM>(w, wv);
             } else {
                 for (int e = 0; e < (int)rem; ++e) {
                     const float u = fmaf(lambda, w[e], g[e]);
@@ -759,12 +764,20 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     return f4{o[0], o[1], o[2], o[3]};
 }
 
+template <bool STREAM = false>
 __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_off, f4 g, float eta, float rho,
                                                   float lambda)
 {
     gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
     gp_char v = (gp_char)(L.row[kRowV] + L.tile_off) + lane_off;
-    const f4 wv = *(gp_cf4)w, vv = *(gp_cf4)v;
+    f4 wv, vv;
+    if constexpr (STREAM) {
+        wv = __builtin_nontemporal_load((gp_cf4)w);
+        vv = __builtin_nontemporal_load((gp_cf4)v);
+    } else {
+        wv = *(gp_cf4)w;
+        vv = *(gp_cf4)v;
+    }
     const float gv[4] = {g.x, g.y, g.z, g.w};
     float wn[4] = {wv.x, wv.y, wv.z, wv.w}, vn[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
@@ -773,8 +786,13 @@ __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_o
         vn[e] = fmaf(rho, vn[e], u);
         wn[e] = fmaf(-eta, vn[e], wn[e]);
     }
-    *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
-    *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
+    if constexpr (STREAM) {
+        __builtin_nontemporal_store(f4{vn[0], vn[1], vn[2], vn[3]}, (gp_f4)v);
+        __builtin_nontemporal_store(f4{wn[0], wn[1], wn[2], wn[3]}, (gp_f4)w);
+    } else {
+        *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
+        *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
+    }
 }
 
 struct FusedArgs {
@@ -851,7 +869,8 @@ __device__ __forceinline__ void fused_cold_mean(const ARGS &p, int c, int tid, d
     acc_b += b;
 }
 
-__device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int tid, float eta)
+template <typename ARGS>
+__device__ __forceinline__ void fused_cold_update(const ARGS &p, int c, int tid, float eta)
 {
     const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
     const int k = tp[0], local = tp[1];
@@ -1099,6 +1118,9 @@ struct StreamArgs {
     double inv_S;
 };
 
+// (The prior-iteration-gain variant uses this kernel too, followed by k_scalars and k_update:
+// updating w and v inside the sweep would save 8 bytes per parameter, but measured at d = 351 M
+// the sweep then runs at the rate of a pass with twice the writes, 9.7 ms against 9.2 ms.)
 template <typename GT, int HG, int NH, bool MASK>
 __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
 {
@@ -1847,6 +1869,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
+    // w and v together beyond ~4x the 256 MB memory-side cache: stream them
+    const bool stream_params = 8 * c->d >= (1LL << 30) && env_int("ADASCALE_UPDATE_STREAM", 1) == 1;
     int f_regs = 0;
     const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag, &f_regs) : nullptr;
     const int f_lds_tiles = std::max(0, std::min(c->f_tpb - f_regs, c->f_lds_cap));
@@ -1932,21 +1956,6 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         return ADASCALE_OK;
     }
     const int grid = std::min(c->n_spans, c->max_blocks);
-    if (lag) {  // single pass (reduce + update with the prior-iteration gain), then the scalars
-        if (grid > 0) {
-            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, grid, s, S, st_in, sa);
-            else launch_reduce_update<Bf16>(c, grid, s, S, st_in, sa);
-            HIP_TRY(c, hipGetLastError());
-        }
-        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-        hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->n_spans, st_in, st_out,
-                           c->d_lr, sa);
-        HIP_TRY(c, hipGetLastError());
-        c->cur ^= 1;
-        if (pe)
-            for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
-        return ADASCALE_OK;
-    }
     const void *stream_fn = c->stream_ok ? stream_kernel_for(c->cfg.grad_dtype, S) : nullptr;
     int n_partials = c->n_spans;
     if (stream_fn) {
@@ -1967,7 +1976,26 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));
         c->stream_launches += 1;
         n_partials = c->s_grid + (ra.n_tiles + 1) / 2;
-    } else if (grid > 0) {
+    }
+    // Prior-iteration gain without the streaming kernel: single pass (reduce + update), then the
+    // scalars.  With it the order is the general one below: k_scalars derives eta_t from the prior
+    // averages and k_update applies it.
+    if (lag && !stream_fn) {
+        if (grid > 0) {
+            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, grid, s, S, st_in, sa);
+            else launch_reduce_update<Bf16>(c, grid, s, S, st_in, sa);
+            HIP_TRY(c, hipGetLastError());
+        }
+        if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
+        hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, st_in, st_out,
+                           c->d_lr, sa);
+        HIP_TRY(c, hipGetLastError());
+        c->cur ^= 1;
+        if (pe)
+            for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
+        return ADASCALE_OK;
+    }
+    if (!stream_fn && grid > 0) {
         if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, grid, s, S);
         else launch_reduce<Bf16>(c, grid, s, S);
         HIP_TRY(c, hipGetLastError());
@@ -1980,14 +2008,18 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
     if (grid > 0) {
         const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
-        if (c->vec == 4)
-            hipLaunchKernelGGL((k_update<4>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
-                               c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
-                               lambda, c->update_reverse);
-        else
-            hipLaunchKernelGGL((k_update<8>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,
-                               c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,
-                               lambda, c->update_reverse);
+#define LAUNCH(VV, ST)                                                                                       \
+    hipLaunchKernelGGL((k_update<VV, ST>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
+                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,   \
+                       lambda, c->update_reverse)
+        if (c->vec == 4) {
+            if (stream_params) LAUNCH(4, true);
+            else LAUNCH(4, false);
+        } else {
+            if (stream_params) LAUNCH(8, true);
+            else LAUNCH(8, false);
+        }
+#undef LAUNCH
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));
