@@ -8,8 +8,8 @@ parameters in 161 tensors (bottleneck-CNN-like shapes), S = 16 fp32 gradient buf
 value        = gradient bytes streamed per second (S*d*4 / step time), GB/s
 roofline     = the dominant kernel against the 8 TB/s HBM peak, algorithmic bytes of one launch /
                its average duration from HIP events on the launch stream inside the timed region:
-               the fused step kernel (whole step, S*d*4 + 24*d bytes) when the library runs the
-               step as one persistent launch, else the reduce kernel (S*d*4 read + 4*d written)
+               the fused step kernel (whole step, S*d*b + 24*d bytes) when the library runs the
+               step as one persistent launch, else the reduce kernel (S*d*b read + 4*d written)
 cpu_baseline = the CPU oracle (OpenMP build of the same source) on the host, one step of the
                same workload
 """
@@ -86,7 +86,8 @@ def main() -> int:
 
     run(args.warmup)
     torch.cuda.synchronize()
-    fused = gpu.uses_fused_step()
+    path = gpu.step_path()
+    fused = path == "fused"
     # Per-kernel HIP events (recorded by the library on the launch stream) for the three-kernel
     # step.  The fused step is a single kernel per step: one pair of events on the launch stream
     # around the K launches gives its average duration without putting an event between every
@@ -125,11 +126,12 @@ def main() -> int:
                 "timing": "HIP events on the launch stream around the K launches / K"}
     elif events and kernel_ms[0]:
         ach = reduce_bytes / (kernel_ms[0] * 1e-3) / 1e9
+        kname = "k_reduce_stream" if path == "streaming" else "k_reduce"
         traffic = None
         tpath = os.path.join(ROOT, "profiles", "traffic.json")
         if os.path.exists(tpath):
-            traffic = json.load(open(tpath)).get(f"k_reduce_cfg{args.config}")
-        roof = {"bound": "hbm", "kernel": "k_reduce", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
+            traffic = json.load(open(tpath)).get(f"{kname}_cfg{args.config}")
+        roof = {"bound": "hbm", "kernel": kname, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": reduce_bytes, "avg_ms": round(kernel_ms[0], 5),
                 "other_kernels_ms": {"k_scalars": round(kernel_ms[1], 5), "k_update": round(kernel_ms[2], 5)},
@@ -168,7 +170,8 @@ def main() -> int:
         "pct_hbm_peak": round(100 * total_bytes / sec / 1e9 / HBM_PEAK_GBPS, 2),
         "grad_elements_per_s": round(S * d / sec, 0),
         "algorithmic_bytes_per_step": total_bytes,
-        "step_path": ("fused" if fused else "three_kernel") + ("+lagged_gain" if args.lagged else ""),
+        "step_path": {"fused": "fused", "streaming": "three_kernel(streaming reduce)", "general": "three_kernel"}[path]
+                     + ("+lagged_gain" if args.lagged else ""),
         "final_state": {"step": st.step, "r": st.r, "tau": st.tau},
         "roofline": roof, "cpu_baseline": cpu,
     }

@@ -44,9 +44,9 @@ enum { ADASCALE_F32 = 0, ADASCALE_BF16 = 1 }; /* gradient element type */
 /* adascale_config.flags */
 enum {
     /* r_t from the averages of PRIOR iterations only, r_0 = 1 (the variant App. B.3 says
-     * its experiments used); eta_t is then known before the gradients are read and the
-     * whole step is one fused pass.  Default (flag clear): current-iteration estimate,
-     * which App. B.3 recommends. */
+     * its experiments used); eta_t is then known before the gradients are read, so the fused
+     * step needs no grid barrier and the general step is a single sweep.  Default (flag
+     * clear): current-iteration estimate, which App. B.3 recommends. */
     ADASCALE_LAGGED_R = 1u,
     /* Estimator of Sec. 3.4: moving averages m1 of A/S and m2 of B,
      * r_t = (m1 + eps) / (m2 + eps), instead of the (s2, m2) estimator of App. B.3. */
@@ -152,9 +152,23 @@ const char *adascale_last_error(const adascale_ctx *ctx);
  * per-parameter traffic of the mean gradient, w and v.  For benchmarks; host only. */
 int64_t adascale_step_bytes(const adascale_ctx *ctx);
 
-/* 1 if this context runs the step as one fused persistent launch that keeps the mean gradient
- * on chip (fp32 gradients, S <= 16, mean gradient mostly fitting in registers + LDS), 0 if it runs the
- * three-kernel step (reduce, scalars, update).  Both compute the same thing. */
+/*
+ * Which implementation the next adascale_step on this context runs; all compute the same thing
+ * (the choice depends on the gradient type, the scale of the moment and the size of the
+ * parameter list, and can be steered with the environment for tests and measurements):
+ *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient on chip as far
+ *                            as it fits (fp32 gradients S <= 32, bf16 S <= 64, and at least
+ *                            about a seventh of the mean gradient fitting in registers + LDS);
+ *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
+ *                            sweep in memory order: same scales, parameter lists far larger
+ *                            than the chip;
+ *   ADASCALE_PATH_GENERAL    three kernels for any scale (or two with ADASCALE_LAGGED_R: one
+ *                            sweep that reduces and updates, then the scalars).
+ */
+enum { ADASCALE_PATH_GENERAL = 0, ADASCALE_PATH_FUSED = 1, ADASCALE_PATH_STREAMING = 2 };
+int adascale_step_path(const adascale_ctx *ctx);
+
+/* 1 if adascale_step_path is ADASCALE_PATH_FUSED, else 0. */
 int adascale_uses_fused_step(const adascale_ctx *ctx);
 
 /*

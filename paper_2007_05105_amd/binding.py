@@ -18,7 +18,8 @@ _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
            "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_bytes",
-           "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step"]
+           "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step",
+           "adascale_step_path"]
 
 
 class AdaScaleError(RuntimeError):
@@ -82,6 +83,8 @@ def load_library() -> C.CDLL:
         lib.adascale_profile_end.restype = C.c_int
         lib.adascale_uses_fused_step.argtypes = [C.c_void_p]
         lib.adascale_uses_fused_step.restype = C.c_int
+        lib.adascale_step_path.argtypes = [C.c_void_p]
+        lib.adascale_step_path.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -167,6 +170,9 @@ class AdaScale:
 
     def uses_fused_step(self) -> bool:
         return bool(self._lib.adascale_uses_fused_step(self._h))
+
+    def step_path(self) -> str:
+        return ("general", "fused", "streaming")[self._lib.adascale_step_path(self._h)]
 
     def step_bytes(self) -> int:
         return int(self._lib.adascale_step_bytes(self._h))

@@ -85,14 +85,12 @@ struct Traits<Bf16> {
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(Bf16 x) { return __uint_as_float((unsigned)x.bits << 16); }
 
-template <int VEC, bool STREAM = false>
+template <int VEC>
 __device__ __forceinline__ void load_f32(const float *p, float (&x)[VEC])
 {
 #pragma unroll
     for (int q = 0; q < VEC / 4; ++q) {
-        f4 t;
-        if constexpr (STREAM) t = __builtin_nontemporal_load((gp_cf4)(p + 4 * q));
-        else t = *(gp_cf4)(p + 4 * q);
+        f4 t = *(gp_cf4)(p + 4 * q);
         x[4 * q] = t.x; x[4 * q + 1] = t.y; x[4 * q + 2] = t.z; x[4 * q + 3] = t.w;
     }
 }
@@ -495,10 +493,9 @@ __global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restric
 
 // ---------------------------------------------------------------------------------------------
 // update: momentum-SGD with eta_t taken from device memory.
-// STREAM: streaming loads and stores throughout, for parameter lists far larger than the caches
-// (measured +7 % there; smaller lists profit from finding w and v in the memory-side cache at
-// the next step, which streaming stores prevent).
-template <int VEC, bool STREAM>
+// (Streaming loads and stores were measured here too: 4 % slower at d = 351 M, and smaller
+// lists profit from finding w and v in the memory-side cache at the next step.)
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ span_first,
                                                      const int *__restrict__ tile_prefix,
                                                      const long long *__restrict__ numel,
@@ -528,17 +525,17 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
             const float *g = reinterpret_cast<const float *>(row[kRowGbar]) + base;
             if (rem >= VEC) {
                 float gv[VEC], wv[VEC], vv[VEC];
-                load_f32<VEC, STREAM>(g, gv);
-                load_f32<VEC, STREAM>(w, wv);
-                load_f32<VEC, STREAM>(v, vv);
+                load_f32<VEC>(g, gv);
+                load_f32<VEC>(w, wv);
+                load_f32<VEC>(v, vv);
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) {
                     const float u = fmaf(lambda, wv[e], gv[e]);
                     vv[e] = fmaf(rho, vv[e], u);
                     wv[e] = fmaf(-eta, vv[e], wv[e]);
                 }
-                store_f32<VEC, STREAM>(v, vv);
-                store_f32<VEC, STREAM>(w, wv);
+                store_f32<VEC>(v, vv);
+                store_f32<VEC>(w, wv);
             } else {
                 for (int e = 0; e < (int)rem; ++e) {
                     const float u = fmaf(lambda, w[e], g[e]);
@@ -764,20 +761,12 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     return f4{o[0], o[1], o[2], o[3]};
 }
 
-template <bool STREAM = false>
 __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_off, f4 g, float eta, float rho,
                                                   float lambda)
 {
     gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
     gp_char v = (gp_char)(L.row[kRowV] + L.tile_off) + lane_off;
-    f4 wv, vv;
-    if constexpr (STREAM) {
-        wv = __builtin_nontemporal_load((gp_cf4)w);
-        vv = __builtin_nontemporal_load((gp_cf4)v);
-    } else {
-        wv = *(gp_cf4)w;
-        vv = *(gp_cf4)v;
-    }
+    const f4 wv = *(gp_cf4)w, vv = *(gp_cf4)v;
     const float gv[4] = {g.x, g.y, g.z, g.w};
     float wn[4] = {wv.x, wv.y, wv.z, wv.w}, vn[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
@@ -786,13 +775,8 @@ __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_o
         vn[e] = fmaf(rho, vn[e], u);
         wn[e] = fmaf(-eta, vn[e], wn[e]);
     }
-    if constexpr (STREAM) {
-        __builtin_nontemporal_store(f4{vn[0], vn[1], vn[2], vn[3]}, (gp_f4)v);
-        __builtin_nontemporal_store(f4{wn[0], wn[1], wn[2], wn[3]}, (gp_f4)w);
-    } else {
-        *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
-        *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
-    }
+    *(gp_f4)v = f4{vn[0], vn[1], vn[2], vn[3]};
+    *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
 }
 
 struct FusedArgs {
@@ -869,8 +853,7 @@ __device__ __forceinline__ void fused_cold_mean(const ARGS &p, int c, int tid, d
     acc_b += b;
 }
 
-template <typename ARGS>
-__device__ __forceinline__ void fused_cold_update(const ARGS &p, int c, int tid, float eta)
+__device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int tid, float eta)
 {
     const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
     const int k = tp[0], local = tp[1];
@@ -1489,7 +1472,7 @@ const void *stream_kernel_for(int dtype, int S)
 // Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
 // so that its workgroups (one per CU in number) also land one per CU.
 constexpr size_t kStreamLdsPad = 96 * 1024;
-constexpr int kFusedMinPct = 25;  // least share of the mean gradient on chip for the fused step
+constexpr int kFusedMinPct = 15;  // least share of the mean gradient on chip for the fused step
 
 // Tile tables of the 512-lane kernels: whole tiles (inside one tensor) and the ragged last tile
 // of each tensor; the streaming reduce kernel's grid and counters.
@@ -1553,7 +1536,7 @@ int setup_fused(adascale_ctx *c)
         if (fused_regs_at(l, 2) <= nt / grid) level = l;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
-    // kernel is the faster one (measured: equal at ~40 % on chip, 10 % ahead at 6 %)
+    // kernel is the faster one (measured crossover: 13-20 % on chip, depending on S; 10 % ahead at 6 %)
     const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level, 2) + std::min(tpb, lds_cap)) / tpb);
     if (c->stream_ok && on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
@@ -1623,7 +1606,16 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
     return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
 }
 
-int adascale_uses_fused_step(const adascale_ctx *c) { return c && c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0) ? 1 : 0; }
+int adascale_step_path(const adascale_ctx *c)
+{
+    if (!c) return ADASCALE_PATH_GENERAL;
+    const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
+    if (c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag)) return ADASCALE_PATH_FUSED;
+    if (c->stream_ok && stream_kernel_for(c->cfg.grad_dtype, c->cfg.S)) return ADASCALE_PATH_STREAMING;
+    return ADASCALE_PATH_GENERAL;
+}
+
+int adascale_uses_fused_step(const adascale_ctx *c) { return adascale_step_path(c) == ADASCALE_PATH_FUSED ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 {
@@ -1869,8 +1861,6 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     const DevState *st_in = c->d_state + c->cur;
     DevState *st_out = c->d_state + (c->cur ^ 1);
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
-    // w and v together beyond ~4x the 256 MB memory-side cache: stream them
-    const bool stream_params = 8 * c->d >= (1LL << 30) && env_int("ADASCALE_UPDATE_STREAM", 1) == 1;
     int f_regs = 0;
     const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag, &f_regs) : nullptr;
     const int f_lds_tiles = std::max(0, std::min(c->f_tpb - f_regs, c->f_lds_cap));
@@ -2008,17 +1998,12 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
     if (grid > 0) {
         const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
-#define LAUNCH(VV, ST)                                                                                       \
-    hipLaunchKernelGGL((k_update<VV, ST>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
-                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,   \
+#define LAUNCH(VV)                                                                                       \
+    hipLaunchKernelGGL((k_update<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
+                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,  \
                        lambda, c->update_reverse)
-        if (c->vec == 4) {
-            if (stream_params) LAUNCH(4, true);
-            else LAUNCH(4, false);
-        } else {
-            if (stream_params) LAUNCH(8, true);
-            else LAUNCH(8, false);
-        }
+        if (c->vec == 4) LAUNCH(4);
+        else LAUNCH(8);
 #undef LAUNCH
         HIP_TRY(c, hipGetLastError());
     }

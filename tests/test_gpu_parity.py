@@ -122,8 +122,9 @@ def test_variants_of_the_estimator(flags):
 
 @pytest.mark.parametrize("S,dtype", [(16, F32), (4, F32), (32, BF16), (5, F32), (64, BF16), (29, F32), (40, F32)])
 def test_lagged_gain_single_pass_medium(S, dtype, step_path):
-    """Prior-iteration gain on shapes that span many tiles per workgroup: the step is one sweep
-    (reduce + update) followed by the scalar kernel."""
+    """Prior-iteration gain on shapes that span many tiles per workgroup (fused step without its
+    grid barrier; streaming reduce, scalars, update; beyond their scales one sweep that reduces
+    and updates, then the scalars)."""
     wl = W.custom([(3_000_000,), (70001,), (513,), (1_200_000,)], S, grad_dtype=dtype, weight_decay=1e-4, theta=0.9,
                   lr_table=W.lr_step_decay(0.1, 64), steps=3, seed=41)
     H.assert_report(H.run_teacher_forced(wl, flags=LAGGED_R, log=log))
@@ -322,10 +323,14 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
         pytest.skip("one run is enough")
     monkeypatch.delenv("ADASCALE_FUSED")
     monkeypatch.delenv("ADASCALE_FUSED_MIN_PCT")
-    for cfg, fused in ((1, True), (3, True), (4, True), (5, False)):
+    for cfg, path in ((1, "fused"), (3, "fused"), (4, "fused"), (5, "streaming")):
         g = H.make_gpu(W.config(cfg))
-        assert g.uses_fused_step() == fused, cfg
+        assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
         g.close()
+    wl = W.config(5)
+    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # no 512-lane instance beyond S = 64
+    assert g.step_path() == "general"
+    g.close()
 
 
 @pytest.mark.parametrize("S,dtype", [(1, F32), (3, F32), (16, F32), (32, F32), (2, BF16), (11, BF16), (64, BF16)])
