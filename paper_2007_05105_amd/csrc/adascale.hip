@@ -717,19 +717,21 @@ struct NoHook {
 // `hook` runs once, right after the second half-group has been issued: work with long latencies
 // of its own (cross-lane sums) hides there behind loads that have to be waited for anyway; LDS
 // writes it makes are published by the barrier at the end.
+// NH = 0: the (even) number of half-groups is the run-time value nh_rt (scales beyond 8 half-groups).
 template <typename GT, int HG, int NH, bool MASK, typename HOOK = NoHook>
 __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next, unsigned lane_off, int S, double inv_S,
                                               typename FGrad<GT>::raw (&xa)[HG], double &acc_a, double &acc_b,
-                                              const HOOK &hook = HOOK())
+                                              const HOOK &hook = HOOK(), int nh_rt = 0)
 {
     static_assert(NH % 2 == 0, "half-groups alternate between two buffers");
     typename FGrad<GT>::Acc acc;
     acc.init();
     typename FGrad<GT>::raw xb[HG];
-    // eight half-groups stay a loop: unrolled they cost more registers than there are
-    constexpr int kUnroll = NH > 4 ? 1 : NH;
+    // eight or more half-groups stay a loop: unrolled they cost more registers than there are
+    constexpr int kUnroll = NH > 4 || NH == 0 ? 1 : NH;
+    const int nh = NH > 0 ? NH : nh_rt;
 #pragma unroll kUnroll
-    for (int h = 0; h < NH; h += 2) {
+    for (int h = 0; h < nh; h += 2) {
         fused_issue<GT, HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (!std::is_same<HOOK, NoHook>::value) {
@@ -738,7 +740,7 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
         }
         fused_accumulate<GT, HG, MASK>(xa, h * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
-        if (h + 2 < NH) fused_issue<GT, HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
+        if (h + 2 < nh) fused_issue<GT, HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
         else fused_issue<GT, HG, MASK>(next, lane_off, 0, S, xa);
         __builtin_amdgcn_sched_barrier(0);
         fused_accumulate<GT, HG, MASK>(xb, (h + 1) * HG, S, acc);
@@ -1098,6 +1100,7 @@ struct StreamArgs {
     unsigned *claim;               // pairs handed out so far in this launch (zero on entry)
     unsigned *claim_next;          // the next launch's counter: zeroed here
     int n_tiles, n_cold, S, row_len;
+    int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
 };
 
@@ -1187,11 +1190,11 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
         const FLoc LN = locate(nxt >= 0 ? 2 * nxt : 2 * cur);  // at the end: a few redundant loads, no branch
         double acc_a = 0.0, acc_b = 0.0;
         f4 m = fused_tile_mean<GT, HG, NH, MASK>(L0, two ? L1 : LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b,
-                                                 wave_partials);
+                                                 wave_partials, p.nh);
         store_mean(L0, m);
         if (prev >= 0) finish(prev);
         if (two) {
-            m = fused_tile_mean<GT, HG, NH, MASK>(L1, LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+            m = fused_tile_mean<GT, HG, NH, MASK>(L1, LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b, NoHook(), p.nh);
             store_mean(L1, m);
         }
         prev_a = acc_a;
@@ -1372,19 +1375,24 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
 // half-groups, which need the registers themselves.
 constexpr int kFRegLevels = 3;
 constexpr int fused_regs_at(int level, int nh) { return level == 0 ? 0 : level == 1 ? 10 : nh > 4 ? 20 : kFRegTiles; }
-constexpr int kFMaxScaleF32 = 32, kFMaxScaleBf16 = 64;
+constexpr int kFMaxScaleF32 = 32, kFMaxScaleBf16 = 64;  // largest scales with a compile-time shape
+constexpr int kStreamMaxScale = 4096;                   // the streaming reduce kernel's run-time shapes
 
-// Half-group shape (HG, NH) for a gradient type and scale; false: no instance.
+// Half-group shape (HG, NH) of the 512-lane kernels for a gradient type and scale; false: none.
+// Up to 8 half-groups the count is a power of two and a template parameter (fused step and
+// streaming reduce kernel); beyond, any even count, taken at run time by the streaming reduce
+// kernel only.
 bool fused_shape(int dtype, int S, int *hg, int *nh)
 {
-    if (S < 1 || S > (dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16)) return false;
+    if (S < 1 || S > kStreamMaxScale) return false;
     // fp32: half-groups of up to 4 16-byte loads; bf16: 8-byte loads, so twice the replicas per
     // half-group for the same bytes in flight
     const int cap = dtype == ADASCALE_F32 ? 4 : 8;
     int h = 1;
     while (h < cap && 2 * h < S) h *= 2;  // smallest HG with 2 * HG >= S, at most cap
     int n = 2;
-    while (h * n < S) n *= 2;
+    while (h * n < S && n < 8) n *= 2;
+    if (h * n < S) n = 2 * ((S + 2 * h - 1) / (2 * h));
     *hg = h;
     *nh = n;
     return true;
@@ -1446,6 +1454,7 @@ const void *stream_kernel_for(int dtype, int S)
 #define KS(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_reduce_stream<GT, HG, NH, MASK>)
     int hg = 0, nh = 0;
     if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
+    if (nh > 8) return dtype == ADASCALE_F32 ? KS(float, 4, 0, true) : KS(Bf16, 8, 0, true);
     const bool exact = hg * nh == S;
     if (dtype == ADASCALE_F32) {
         switch (hg * 100 + nh) {
@@ -1505,7 +1514,7 @@ int setup_tiles(adascale_ctx *c)
     const long long n_pairs = ((long long)nt + 1) / 2;
     c->s_grid = (int)std::max<long long>(1, std::min<long long>(std::max<long long>(n_pairs, (long long)nc),
                                                                std::min(c->n_cus, kFMaxGrid)));
-    const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
+    const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
         const void *fn = stream_kernel_for(c->cfg.grad_dtype, S);
         if (fn) HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsPad));
@@ -1961,6 +1970,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.n_cold = (int)c->ctiles.size();
         ra.S = S;
         ra.row_len = row_len;
+        int hg = 0;
+        (void)fused_shape(c->cfg.grad_dtype, S, &hg, &ra.nh);
         ra.inv_S = 1.0 / (double)S;
         void *args[] = {&ra};
         HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));

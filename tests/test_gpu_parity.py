@@ -22,19 +22,23 @@ def log(msg):
     print(msg, flush=True)
 
 
-@pytest.fixture(autouse=True, params=["fused", "three_kernel"])
+@pytest.fixture(autouse=True, params=["fused", "three_kernel", "general"])
 def step_path(request, monkeypatch):
-    """Every test runs once per implementation of the step: the fused persistent launch (S <= 32
-    for fp32 gradients, <= 64 for bf16: the mean gradient stays on chip as far as it fits; forced
-    here even where the library would not choose it) and the three-kernel step (forced here; also
-    what larger scales and parameter lists far larger than the chip get)."""
+    """Every test runs once per implementation of the step, forced here even where the library
+    would choose another: the fused persistent launch (S <= 32 for fp32 gradients, <= 64 for
+    bf16; the mean gradient stays on chip as far as it fits), the three-kernel step with the
+    streaming reduce kernel (what parameter lists far larger than the chip and larger scales
+    get), and the general three-kernel step (any scale)."""
     monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
+    monkeypatch.setenv("ADASCALE_STREAM", "2" if request.param == "general" else "1")
     monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
     return request.param
 
 
 def expect_path(gpu, step_path, dtype=F32):
-    assert gpu.uses_fused_step() == (step_path == "fused" and gpu.S <= (32 if dtype == F32 else 64))
+    fused = step_path == "fused" and gpu.S <= (32 if dtype == F32 else 64)
+    assert gpu.uses_fused_step() == fused
+    assert gpu.step_path() == ("fused" if fused else "general" if step_path == "general" else "streaming")
 
 
 # ------------------------------------------------------------------ small shapes, every path
@@ -323,17 +327,22 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
         pytest.skip("one run is enough")
     monkeypatch.delenv("ADASCALE_FUSED")
     monkeypatch.delenv("ADASCALE_FUSED_MIN_PCT")
+    monkeypatch.delenv("ADASCALE_STREAM")
     for cfg, path in ((1, "fused"), (3, "fused"), (4, "fused"), (5, "streaming")):
         g = H.make_gpu(W.config(cfg))
         assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
         g.close()
     wl = W.config(5)
-    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # no 512-lane instance beyond S = 64
+    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # the fused step stops at S = 64
+    assert g.step_path() == "streaming"
+    g.close()
+    g = AdaScale([1000], 5000, [0.1])                             # beyond every 512-lane shape
     assert g.step_path() == "general"
     g.close()
 
 
-@pytest.mark.parametrize("S,dtype", [(1, F32), (3, F32), (16, F32), (32, F32), (2, BF16), (11, BF16), (64, BF16)])
+@pytest.mark.parametrize("S,dtype", [(1, F32), (3, F32), (16, F32), (32, F32), (33, F32), (50, F32), (2, BF16), (11, BF16),
+                                     (64, BF16), (65, BF16), (128, BF16), (150, BF16)])
 def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, step_path):
     """Three-kernel step on a list with thousands of tile pairs (each workgroup claims dozens),
     an odd number of whole tiles, ragged tails and tensors smaller than a tile."""
