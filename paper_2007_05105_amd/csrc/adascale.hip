@@ -561,13 +561,13 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
 //
 // Tiles here are 512 lanes x 4 elements.  Tiles that lie wholly inside a tensor ("full") take
 // the hot path: straight-line code without per-lane predicates.  Slot q of workgroup b is full
-// tile q * gridDim.x + b; slots [0, 30) live in VGPRs, the next lds_tiles slots in LDS, and any
+// tile q * gridDim.x + b; slots [0, R) live in VGPRs (R up to 44), the next lds_tiles slots in LDS, and any
 // further slots go through the HBM scratch like in the three-kernel step.  The ragged last tile
 // of each tensor ("cold", at most one per tensor) takes a simple predicated path through the
 // HBM scratch.
 constexpr int kFThreads = 512;                 // 8 waves: 2 per SIMD, up to 256 VGPRs each
 constexpr int kFWaves = kFThreads / kWave;
-constexpr int kFRegTiles = 30;                 // f4 per lane kept in VGPRs
+constexpr int kFRegTiles = 44;                 // most f4 per lane kept in VGPRs (176 of the 256 registers)
 constexpr int kFTile = kFThreads * 4;          // elements per tile (fp32 gradients)
 constexpr int kFMaxGrid = 256;                 // workgroups (one per CU) = partial slots
 constexpr long long kFSpinLimit = 1LL << 22;   // bounded wait at the grid barrier
@@ -727,25 +727,37 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     typename FGrad<GT>::Acc acc;
     acc.init();
     typename FGrad<GT>::raw xb[HG];
-    // eight or more half-groups stay a loop: unrolled they cost more registers than there are
+    // Eight or more half-groups stay a loop (unrolled they cost more registers than there are).
+    // Its body must be one basic block: what the second issue of a pair fetches -- the next
+    // half-group of this tile or, after the last pair, the first one of the next tile -- is
+    // chosen with scalar selects, not a branch (with a branch the compiler sinks the accumulation
+    // below it, the loads then overwrite registers still in use, and it drains the memory
+    // pipeline every iteration to stay correct).
     constexpr int kUnroll = NH > 4 || NH == 0 ? 1 : NH;
     const int nh = NH > 0 ? NH : nh_rt;
-#pragma unroll kUnroll
-    for (int h = 0; h < nh; h += 2) {
+    auto pair = [&](int h, auto &&between) {
         fused_issue<GT, HG, MASK>(cur, lane_off, (h + 1) * HG, S, xb);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (!std::is_same<HOOK, NoHook>::value) {
-            if (h == 0) hook();
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        between();
         fused_accumulate<GT, HG, MASK>(xa, h * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
-        if (h + 2 < nh) fused_issue<GT, HG, MASK>(cur, lane_off, (h + 2) * HG, S, xa);
-        else fused_issue<GT, HG, MASK>(next, lane_off, 0, S, xa);
+        const bool last = h + 2 >= nh;
+        const FLoc from{last ? next.row : cur.row, last ? next.tile_off : cur.tile_off};
+        fused_issue<GT, HG, MASK>(from, lane_off, last ? 0 : (h + 2) * HG, S, xa);
         __builtin_amdgcn_sched_barrier(0);
         fused_accumulate<GT, HG, MASK>(xb, (h + 1) * HG, S, acc);
         __builtin_amdgcn_sched_barrier(0);
+    };
+    int h = 0;
+    if constexpr (!std::is_same<HOOK, NoHook>::value) {  // first pair apart, with the hook
+        pair(0, [&] {
+            hook();
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        h = 2;
     }
+#pragma unroll kUnroll
+    for (; h < nh; h += 2) pair(h, [] {});
     float o[4];
     double b = 0.0;
 #pragma unroll
@@ -756,6 +768,10 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     }
     acc_a += acc.a;
     acc_b += b;
+    // The sums are brought up to date here: left free, the compiler postpones the squares of the
+    // means of every retained tile to the end of phase 1 and keeps their fp64 values alive until
+    // then (8 more registers per retained tile).
+    asm volatile("" : "+v"(acc_a), "+v"(acc_b));
     // Keep the 8 waves of the workgroup on the same tile: left alone, the older waves win the
     // arbitration for the memory pipeline and the workgroup then waits for its youngest wave.
     if constexpr (std::is_same<HOOK, NoHook>::value) __builtin_amdgcn_s_barrier();
@@ -794,6 +810,7 @@ struct FusedArgs {
     unsigned long long barrier_target;
     int *fault;                    // set when the bounded wait at the barrier gave up
     int n_tiles, n_cold, tiles_per_block, lds_tiles, S, row_len;
+    int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
     float rho, lambda;
     ScalarArgs sc;
@@ -925,7 +942,8 @@ __device__ __forceinline__ void fused_regs_phase1(const FCtx<R> &cx, unsigned la
 {
     if constexpr (Q < R) {
         const FLoc next = cx.locate(cx.after(Q));
-        keep[Q] = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, cx.p.S, cx.p.inv_S, xa, acc_a, acc_b);
+        keep[Q] = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, cx.p.S, cx.p.inv_S, xa, acc_a, acc_b, NoHook(),
+                                                    cx.p.nh);
         cur = next;
         fused_regs_phase1<GT, HG, NH, MASK, R, Q + 1>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
@@ -973,14 +991,14 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         fused_issue<GT, HG, MASK>(cur, lane_off, 0, p.S, xa);
         for (int q = q_hbm; q < n_valid; ++q) {
             const FLoc next = cx.locate(cx.after(q));
-            const f4 m = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+            const f4 m = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b, NoHook(), p.nh);
             __builtin_nontemporal_store(m, (gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off));
             cur = next;
         }
         for (int q = R; q < q_lds_end; ++q) {
             const FLoc next = cx.locate(cx.after(q));
             lds_gbar[(q - R) * kFThreads + tid] =
-                fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b);
+                fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b, NoHook(), p.nh);
             cur = next;
         }
         fused_regs_phase1<GT, HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
@@ -1371,17 +1389,15 @@ bool device_range_ok(const void *p, size_t bytes, int device, uintptr_t &lo, uin
 }
 
 // Register-slot counts the fused kernel is instantiated for (the host uses the largest one that
-// every workgroup can fill): three levels, the top one lower for the instances with eight
-// half-groups, which need the registers themselves.
-constexpr int kFRegLevels = 3;
-constexpr int fused_regs_at(int level, int nh) { return level == 0 ? 0 : level == 1 ? 10 : nh > 4 ? 20 : kFRegTiles; }
+// every workgroup can fill).
+constexpr int kFRegLevels = 4;
+constexpr int fused_regs_at(int level) { return level == 0 ? 0 : level == 1 ? 10 : level == 2 ? 30 : kFRegTiles; }
 constexpr int kFMaxScaleF32 = 32, kFMaxScaleBf16 = 64;  // largest scales with a compile-time shape
-constexpr int kStreamMaxScale = 4096;                   // the streaming reduce kernel's run-time shapes
+constexpr int kStreamMaxScale = 4096;                   // largest scale of the run-time shapes
 
 // Half-group shape (HG, NH) of the 512-lane kernels for a gradient type and scale; false: none.
-// Up to 8 half-groups the count is a power of two and a template parameter (fused step and
-// streaming reduce kernel); beyond, any even count, taken at run time by the streaming reduce
-// kernel only.
+// The count is the smallest even one that covers S; 2, 4 and 8 are template parameters, any other
+// count is taken at run time (one more instance per kernel family and gradient type).
 bool fused_shape(int dtype, int S, int *hg, int *nh)
 {
     if (S < 1 || S > kStreamMaxScale) return false;
@@ -1390,11 +1406,8 @@ bool fused_shape(int dtype, int S, int *hg, int *nh)
     const int cap = dtype == ADASCALE_F32 ? 4 : 8;
     int h = 1;
     while (h < cap && 2 * h < S) h *= 2;  // smallest HG with 2 * HG >= S, at most cap
-    int n = 2;
-    while (h * n < S && n < 8) n *= 2;
-    if (h * n < S) n = 2 * ((S + 2 * h - 1) / (2 * h));
     *hg = h;
-    *nh = n;
+    *nh = 2 * ((S + 2 * h - 1) / (2 * h));
     return true;
 }
 
@@ -1407,9 +1420,10 @@ int padded_scale(int dtype, int S)
 template <int LEVEL, bool LAG>
 const void *fused_kernel_at(int dtype, int S)
 {
-#define KF(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_fused<GT, HG, NH, MASK, fused_regs_at(LEVEL, NH), LAG>)
+#define KF(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_fused<GT, HG, NH, MASK, fused_regs_at(LEVEL), LAG>)
     int hg = 0, nh = 0;
     if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
+    if (nh != 2 && nh != 4 && nh != 8) return dtype == ADASCALE_F32 ? KF(float, 4, 0, true) : KF(Bf16, 8, 0, true);
     const bool exact = hg * nh == S;
     if (dtype == ADASCALE_F32) {
         switch (hg * 100 + nh) {
@@ -1439,11 +1453,12 @@ const void *fused_kernel_for(int dtype, int S, int level, bool lag, int *regs = 
 {
     int hg = 0, nh = 0;
     if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
-    if (regs) *regs = fused_regs_at(level, nh);
+    if (regs) *regs = fused_regs_at(level);
     switch (level) {
     case 0: return lag ? fused_kernel_at<0, true>(dtype, S) : fused_kernel_at<0, false>(dtype, S);
     case 1: return lag ? fused_kernel_at<1, true>(dtype, S) : fused_kernel_at<1, false>(dtype, S);
     case 2: return lag ? fused_kernel_at<2, true>(dtype, S) : fused_kernel_at<2, false>(dtype, S);
+    case 3: return lag ? fused_kernel_at<3, true>(dtype, S) : fused_kernel_at<3, false>(dtype, S);
     default: return nullptr;
     }
 }
@@ -1454,7 +1469,7 @@ const void *stream_kernel_for(int dtype, int S)
 #define KS(GT, HG, NH, MASK) reinterpret_cast<const void *>(k_reduce_stream<GT, HG, NH, MASK>)
     int hg = 0, nh = 0;
     if (!fused_shape(dtype, S, &hg, &nh)) return nullptr;
-    if (nh > 8) return dtype == ADASCALE_F32 ? KS(float, 4, 0, true) : KS(Bf16, 8, 0, true);
+    if (nh != 2 && nh != 4 && nh != 8) return dtype == ADASCALE_F32 ? KS(float, 4, 0, true) : KS(Bf16, 8, 0, true);
     const bool exact = hg * nh == S;
     if (dtype == ADASCALE_F32) {
         switch (hg * 100 + nh) {
@@ -1542,14 +1557,14 @@ int setup_fused(adascale_ctx *c)
     const int tpb = (int)((nt + grid - 1) / grid);
     int level = 0;  // register-slot level: the highest whose (largest) slot count every workgroup can fill
     for (int l = 0; l < kFRegLevels; ++l)
-        if (fused_regs_at(l, 2) <= nt / grid) level = l;
+        if (fused_regs_at(l) <= nt / grid) level = l;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
     // kernel is the faster one (measured crossover: 13-20 % on chip, depending on S; 10 % ahead at 6 %)
-    const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level, 2) + std::min(tpb, lds_cap)) / tpb);
+    const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level) + std::min(tpb, lds_cap)) / tpb);
     if (c->stream_ok && on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
-    const int max_scale = c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16;
+    const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
         const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
         if (!fn) continue;
@@ -1892,6 +1907,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.lds_tiles = f_lds_tiles;
         fa.S = S;
         fa.row_len = row_len;
+        int f_hg = 0;
+        (void)fused_shape(c->cfg.grad_dtype, S, &f_hg, &fa.nh);
         fa.inv_S = 1.0 / (double)S;
         fa.rho = (float)c->cfg.momentum;
         fa.lambda = (float)c->cfg.weight_decay;

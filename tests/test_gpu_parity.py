@@ -25,10 +25,10 @@ def log(msg):
 @pytest.fixture(autouse=True, params=["fused", "three_kernel", "general"])
 def step_path(request, monkeypatch):
     """Every test runs once per implementation of the step, forced here even where the library
-    would choose another: the fused persistent launch (S <= 32 for fp32 gradients, <= 64 for
-    bf16; the mean gradient stays on chip as far as it fits), the three-kernel step with the
-    streaming reduce kernel (what parameter lists far larger than the chip and larger scales
-    get), and the general three-kernel step (any scale)."""
+    would choose another: the fused persistent launch (the mean gradient stays on chip as far as
+    it fits), the three-kernel step with the streaming reduce kernel (what parameter lists far
+    larger than the chip get), and the general three-kernel step (any scale; the other two stop
+    at S = 4096)."""
     monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
     monkeypatch.setenv("ADASCALE_STREAM", "2" if request.param == "general" else "1")
     monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
@@ -36,7 +36,7 @@ def step_path(request, monkeypatch):
 
 
 def expect_path(gpu, step_path, dtype=F32):
-    fused = step_path == "fused" and gpu.S <= (32 if dtype == F32 else 64)
+    fused = step_path == "fused"
     assert gpu.uses_fused_step() == fused
     assert gpu.step_path() == ("fused" if fused else "general" if step_path == "general" else "streaming")
 
@@ -56,8 +56,9 @@ def test_small_multi_tensor_all_scales(S, dtype):
 
 
 @pytest.mark.parametrize("S,dtype", [(1, F32), (2, F32), (3, F32), (4, F32), (7, F32), (8, F32), (13, F32), (16, F32),
-                                     (23, F32), (32, F32),
-                                     (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16), (51, BF16), (64, BF16)])
+                                     (23, F32), (32, F32), (33, F32), (57, F32),
+                                     (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16), (51, BF16), (64, BF16),
+                                     (65, BF16), (130, BF16)])
 def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, dtype, step_path, monkeypatch):
     """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
     if step_path != "fused":
@@ -333,8 +334,11 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
         assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
         g.close()
     wl = W.config(5)
-    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # the fused step stops at S = 64
+    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # run-time number of half-groups
     assert g.step_path() == "streaming"
+    g.close()
+    g = AdaScale(W.config(3).numel, 128, wl.lr_table, grad_dtype=BF16)
+    assert g.step_path() == "fused"
     g.close()
     g = AdaScale([1000], 5000, [0.1])                             # beyond every 512-lane shape
     assert g.step_path() == "general"
