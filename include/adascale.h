@@ -157,11 +157,11 @@ int64_t adascale_step_bytes(const adascale_ctx *ctx);
  * (the choice depends on the gradient type, the scale of the moment and the size of the
  * parameter list, and can be steered with the environment for tests and measurements):
  *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient on chip as far
- *                            as it fits (fp32 gradients S <= 32, bf16 S <= 64, and at least
- *                            about a seventh of the mean gradient fitting in registers + LDS);
+ *                            as it fits (S <= 4096 and at least about a seventh of the mean
+ *                            gradient fitting in registers + LDS);
  *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
- *                            sweep in memory order: same scales, parameter lists far larger
- *                            than the chip;
+ *                            sweep in memory order: S <= 4096, parameter lists far larger than
+ *                            the chip;
  *   ADASCALE_PATH_GENERAL    three kernels for any scale (or two with ADASCALE_LAGGED_R: one
  *                            sweep that reduces and updates, then the scalars).
  */

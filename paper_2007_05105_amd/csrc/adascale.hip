@@ -1,23 +1,20 @@
-// AdaScale SGD step for MI355X (gfx950): HIP kernels and the C ABI declared in adascale.h.
+// AdaScale SGD step for MI355X (gfx950): host side of the C ABI declared in adascale.h, and the
+// choice and launch of the kernels (adascale_device.h).
 //
 // A step never needs the host.  In its general form it is three launches on the caller's stream:
 //   reduce  : one streaming pass over the S gradient buffers; writes the mean gradient
-//             (Sec. 2, Algorithm 1) and per-workgroup fp64 partial sums of A = sum_i ||g_i||^2
-//             and B = ||gbar||^2 (App. B.3);
+//             (Sec. 2, Algorithm 1) and fp64 partial sums of A = sum_i ||g_i||^2 and
+//             B = ||gbar||^2 (App. B.3) into slots fixed by the data, not by the scheduling;
 //   scalars : one workgroup sums the partials in a fixed order and evaluates the estimates,
 //             clamps, moving averages, gain ratio r_t, eta_t and tau (App. B.3, eq. 3, Sec. 3.2);
 //   update  : v <- rho v + gbar + lambda w, w <- w - eta_t v with eta_t read from device memory.
-// When the mean gradient fits on chip (fp32 gradients, see "fused step" below) the same work is
-// one persistent launch that keeps it in registers and LDS across a grid barrier.
+// Three implementations exist (adascale_step_path): the fused step, one persistent launch that
+// keeps the mean gradient in registers and LDS across a grid barrier (parameter lists up to
+// several times the chip's capacity); the three kernels above with a persistent, memory-ordered
+// reduce kernel (larger lists); and the three kernels in their general form (any scale).
 // The path is bandwidth bound (about half a flop per byte), so there is no matrix-core work:
-// the kernels are 16-byte-per-lane coalesced streams, 64-lane shuffle reductions and fp64
+// the kernels are 8- or 16-byte-per-lane coalesced streams, 64-lane shuffle reductions and fp64
 // accumulation of exact squares.
-//
-// Work decomposition: every tensor is cut into tiles of 256 lanes x 16 bytes of gradient; the
-// tiles of all tensors form one list, cut into spans of `span_tiles` consecutive tiles.  A
-// workgroup handles whole spans and every workgroup writes its span partial to a slot fixed by
-// the span, so the reduction result does not depend on scheduling.
-
 
 #include "adascale_device.h"
 
