@@ -80,6 +80,7 @@ struct adascale_ctx {
     bool tiles_ok = false, stream_ok = false;
     int n_cus = 0, s_grid = 0;
     unsigned *d_claim = nullptr;         // two counters: a launch uses one and zeroes the other
+    bool stream_momentum = true;         // the sweep writes the new momentum instead of the mean gradient
     unsigned long long stream_launches = 0;
 
     DevState *h_state = nullptr;    // pinned
@@ -226,7 +227,7 @@ const void *stream_kernel_for(int dtype, int S)
 // Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
 // so that its workgroups (one per CU in number) also land one per CU.
 constexpr size_t kStreamLdsPad = 96 * 1024;
-constexpr int kFusedMinPct = 15;  // least share of the mean gradient on chip for the fused step
+constexpr int kFusedMinPct = 20;  // least share of the mean gradient on chip for the fused step
 
 // Tile tables of the 512-lane kernels: whole tiles (inside one tensor) and the ragged last tile
 // of each tensor; the streaming reduce kernel's grid and counters.
@@ -266,6 +267,7 @@ int setup_tiles(adascale_ctx *c)
     }
     HIP_TRY(c, hipMalloc(&c->d_claim, 2 * sizeof(unsigned)));
     HIP_TRY(c, hipMemset(c->d_claim, 0, 2 * sizeof(unsigned)));
+    c->stream_momentum = env_int("ADASCALE_STREAM_MOMENTUM", 1) == 1;  // 2: mean gradient through the scratch
     c->stream_ok = true;
     return ADASCALE_OK;
 }
@@ -290,7 +292,7 @@ int setup_fused(adascale_ctx *c)
         if (fused_regs_at(l) <= nt / grid) level = l;
     const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
-    // kernel is the faster one (measured crossover: 13-20 % on chip, depending on S; 10 % ahead at 6 %)
+    // kernel is the faster one (measured crossover: 13-25 % on chip, depending on S and gradient type)
     const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level) + std::min(tpb, lds_cap)) / tpb);
     if (c->stream_ok && on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
@@ -719,6 +721,9 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.row_len = row_len;
         int hg = 0;
         (void)fused_shape(c->cfg.grad_dtype, S, &hg, &ra.nh);
+        ra.momentum = c->stream_momentum ? 1 : 0;
+        ra.rho = (float)c->cfg.momentum;
+        ra.lambda = (float)c->cfg.weight_decay;
         ra.inv_S = 1.0 / (double)S;
         void *args[] = {&ra};
         HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));
@@ -760,9 +765,18 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     hipLaunchKernelGGL((k_update<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
                        c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,  \
                        lambda, c->update_reverse)
-        if (c->vec == 4) LAUNCH(4);
-        else LAUNCH(8);
+#define LAUNCH_APPLY(VV)                                                                                    \
+    hipLaunchKernelGGL((k_apply<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,  \
+                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len)
+        if (stream_fn && c->stream_momentum) {
+            if (c->vec == 4) LAUNCH_APPLY(4);
+            else LAUNCH_APPLY(8);
+        } else {
+            if (c->vec == 4) LAUNCH(4);
+            else LAUNCH(8);
+        }
 #undef LAUNCH
+#undef LAUNCH_APPLY
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));

@@ -418,6 +418,47 @@ __device__ __forceinline__ float lagged_eta(const DevState *__restrict__ st, con
 }
 
 // ---------------------------------------------------------------------------------------------
+// apply: w <- w - eta_t v, for the steps whose gradient sweep has already left the new
+// momentum in v (12 bytes per parameter instead of the 20 of k_update).
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void k_apply(const int *__restrict__ span_first,
+                                                    const int *__restrict__ tile_prefix,
+                                                    const long long *__restrict__ numel,
+                                                    const unsigned long long *__restrict__ ptrs,
+                                                    const DevState *__restrict__ st, int n_tiles, int span_tiles,
+                                                    int n_spans, int row_len)
+{
+    constexpr int TILE = kThreads * VEC;
+    const int tid = threadIdx.x;
+    const float eta = st->eta_f32;
+
+    for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
+        const int t0 = span * span_tiles;
+        const int t1 = min(t0 + span_tiles, n_tiles);
+        int k = span_first[span];
+        for (int t = t0; t < t1; ++t) {
+            while (t >= tile_prefix[k + 1]) ++k;
+            const long long base = (long long)(t - tile_prefix[k]) * TILE + (long long)tid * VEC;
+            const long long rem = numel[k] - base;
+            if (rem <= 0) continue;
+            const unsigned long long *row = ptrs + (size_t)k * row_len;
+            float *w = reinterpret_cast<float *>(row[kRowW]) + base;
+            const float *v = reinterpret_cast<const float *>(row[kRowV]) + base;
+            if (rem >= VEC) {
+                float wv[VEC], vv[VEC];
+                load_f32<VEC>(w, wv);
+                load_f32<VEC>(v, vv);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) wv[e] = fmaf(-eta, vv[e], wv[e]);
+                store_f32<VEC>(w, wv);
+            } else {
+                for (int e = 0; e < (int)rem; ++e) w[e] = fmaf(-eta, v[e], w[e]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // single pass (prior-iteration gain): reduce and update in one sweep, S*d*b + 16*d bytes.  The
 // mean gradient never goes to memory; k_scalars afterwards folds A and B into the averages.
 template <typename GT, int HG>
@@ -783,6 +824,14 @@ __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_o
     *(gp_f4)w = f4{wn[0], wn[1], wn[2], wn[3]};
 }
 
+// w <- w - eta v for one full tile whose new momentum is already in v.
+__device__ __forceinline__ void fused_tile_apply(const FLoc &L, unsigned lane_off, float eta)
+{
+    gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
+    const f4 wv = *(gp_cf4)w, vv = *(gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off);
+    *(gp_f4)w = f4{fmaf(-eta, vv.x, wv.x), fmaf(-eta, vv.y, wv.y), fmaf(-eta, vv.z, wv.z), fmaf(-eta, vv.w, wv.w)};
+}
+
 struct FusedArgs {
     const FTile *tiles;            // full tiles   } read through the constant address space
     const FTile *cold;             // ragged tiles }
@@ -975,10 +1024,25 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         const int q_first = q_hbm < n_valid ? q_hbm : (R < q_lds_end ? R : 0);
         FLoc cur = cx.locate(q_first);
         fused_issue<GT, HG, MASK>(cur, lane_off, 0, p.S, xa);
+        // Tiles beyond the chip's capacity: their sweep leaves the new momentum
+        // v <- rho v + gbar + lambda w (which does not depend on eta_t) in v, and phase 2 only
+        // applies it.  That writes 8 bytes per parameter where a round trip of the mean gradient
+        // through a scratch writes 12, and writes are what this memory system charges most for.
+        // v (and w when there is weight decay) are requested before the tile's gradients, so
+        // they have arrived when the mean is known.
+        const bool decay = p.lambda != 0.f;
         for (int q = q_hbm; q < n_valid; ++q) {
             const FLoc next = cx.locate(cx.after(q));
+            gp_char vp = (gp_char)(cur.row[kRowV] + cur.tile_off) + lane_off;
+            const f4 vv = __builtin_nontemporal_load((gp_cf4)vp);
+            f4 wv = {0.f, 0.f, 0.f, 0.f};
+            if (decay) wv = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(cur.row[kRowW] + cur.tile_off) + lane_off));
             const f4 m = fused_tile_mean<GT, HG, NH, MASK>(cur, next, lane_off, p.S, p.inv_S, xa, acc_a, acc_b, NoHook(), p.nh);
-            __builtin_nontemporal_store(m, (gp_f4)((gp_char)(cur.row[kRowGbar] + cur.tile_off) + lane_off));
+            const float g4[4] = {m.x, m.y, m.z, m.w}, v4[4] = {vv.x, vv.y, vv.z, vv.w}, w4[4] = {wv.x, wv.y, wv.z, wv.w};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = fmaf(p.rho, v4[e], decay ? fmaf(p.lambda, w4[e], g4[e]) : g4[e]);
+            __builtin_nontemporal_store(f4{o[0], o[1], o[2], o[3]}, (gp_f4)vp);
             cur = next;
         }
         for (int q = R; q < q_lds_end; ++q) {
@@ -1070,11 +1134,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
     for (int q = R; q < q_lds_end; ++q)
         fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
-    for (int q = q_hbm; q < n_valid; ++q) {
-        const FLoc L = cx.locate(q);
-        const f4 g = *(gp_cf4)((gp_cchar)(L.row[kRowGbar] + L.tile_off) + lane_off);
-        fused_tile_update(L, lane_off, g, eta, p.rho, p.lambda);
-    }
+    for (int q = q_hbm; q < n_valid; ++q) fused_tile_apply(cx.locate(q), lane_off, eta);
     for (int c = b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);
     FUSED_STAMP(4);
 }
@@ -1106,7 +1166,31 @@ struct StreamArgs {
     int n_tiles, n_cold, S, row_len;
     int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
+    // momentum: 0 = write the mean gradient to the scratch (k_update follows); 1 = write
+    // v <- rho v + gbar + lambda w, which does not depend on eta_t, in place of it (k_apply
+    // follows).  Same arithmetic, same results; the step then writes 8 instead of 12 bytes per
+    // parameter, reads v here instead of the mean gradient later, and needs no scratch.
+    int momentum;
+    float rho, lambda;
 };
+
+// Ragged tile, momentum variant: turn the mean gradient the same lane has just left in the
+// scratch into the new momentum.
+template <typename ARGS>
+__device__ __forceinline__ void fused_cold_momentum(const ARGS &p, int c, int tid)
+{
+    const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
+    const int k = tp[0], local = tp[1];
+    cp_u64 row = (cp_u64)p.ptrs + (size_t)k * p.row_len;
+    const long long first = (long long)local * kFTile + (long long)tid * 4;
+    const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
+    if (rem <= 0) return;
+    const AS_GLOBAL float *w = (const AS_GLOBAL float *)row[kRowW] + first;
+    AS_GLOBAL float *v = (AS_GLOBAL float *)row[kRowV] + first;
+    const AS_GLOBAL float *gb = (const AS_GLOBAL float *)row[kRowGbar] + first;
+    const int n = rem < 4 ? (int)rem : 4;
+    for (int e = 0; e < n; ++e) v[e] = fmaf(p.rho, v[e], fmaf(p.lambda, w[e], gb[e]));
+}
 
 // (The prior-iteration-gain variant uses this kernel too, followed by k_scalars and k_update:
 // updating w and v inside the sweep would save 8 bytes per parameter, but measured at d = 351 M
@@ -1136,7 +1220,10 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
     // ragged tiles -> this workgroup's slot
     {
         double acc_a = 0.0, acc_b = 0.0;
-        for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, StreamArgs>(p, c, tid, acc_a, acc_b);
+        for (int c = b; c < p.n_cold; c += G) {
+            fused_cold_mean<GT, HG, StreamArgs>(p, c, tid, acc_a, acc_b);
+            if (p.momentum) fused_cold_momentum(p, c, tid);
+        }
         acc_a = wave_sum(acc_a);
         acc_b = wave_sum(acc_b);
         if ((tid & (kWave - 1)) == 0) {
@@ -1157,8 +1244,25 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
         const AS_CONST int *tp = (const AS_CONST int *)p.tiles + 2 * (size_t)t;
         return FLoc{(cp_u64)p.ptrs + (size_t)tp[0] * row_len, (unsigned long long)tp[1] * (kFTile * 4ULL)};
     };
-    auto store_mean = [&](const FLoc &L, f4 m) {
-        __builtin_nontemporal_store(m, (gp_f4)((gp_char)(L.row[kRowGbar] + L.tile_off) + lane_off));
+    // Momentum variant: v (and w when there is weight decay) of a tile are requested before its
+    // gradients, so they have arrived when the mean is known.
+    const bool momentum = p.momentum != 0, decay = p.lambda != 0.f;
+    auto fetch_params = [&](const FLoc &L, f4 &vv, f4 &wv) {
+        if (momentum) {
+            vv = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off));
+            if (decay) wv = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowW] + L.tile_off) + lane_off));
+        }
+    };
+    auto store_mean = [&](const FLoc &L, f4 m, f4 vv, f4 wv) {
+        if (momentum) {
+            const float g4[4] = {m.x, m.y, m.z, m.w}, v4[4] = {vv.x, vv.y, vv.z, vv.w}, w4[4] = {wv.x, wv.y, wv.z, wv.w};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = fmaf(p.rho, v4[e], decay ? fmaf(p.lambda, w4[e], g4[e]) : g4[e]);
+            __builtin_nontemporal_store(f4{o[0], o[1], o[2], o[3]}, (gp_f4)((gp_char)(L.row[kRowV] + L.tile_off) + lane_off));
+        } else {
+            __builtin_nontemporal_store(m, (gp_f4)((gp_char)(L.row[kRowGbar] + L.tile_off) + lane_off));
+        }
     };
     auto finish = [&](int pair) {  // after a barrier: the pair's contribution in wave order
         if (tid < 2) {
@@ -1193,13 +1297,16 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
         const FLoc L1 = locate(two ? 2 * cur + 1 : 2 * cur);
         const FLoc LN = locate(nxt >= 0 ? 2 * nxt : 2 * cur);  // at the end: a few redundant loads, no branch
         double acc_a = 0.0, acc_b = 0.0;
+        f4 vv = {0.f, 0.f, 0.f, 0.f}, wv = {0.f, 0.f, 0.f, 0.f};
+        fetch_params(L0, vv, wv);
         f4 m = fused_tile_mean<GT, HG, NH, MASK>(L0, two ? L1 : LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b,
                                                  wave_partials, p.nh);
-        store_mean(L0, m);
+        store_mean(L0, m, vv, wv);
         if (prev >= 0) finish(prev);
         if (two) {
+            fetch_params(L1, vv, wv);
             m = fused_tile_mean<GT, HG, NH, MASK>(L1, LN, lane_off, p.S, p.inv_S, xa, acc_a, acc_b, NoHook(), p.nh);
-            store_mean(L1, m);
+            store_mean(L1, m, vv, wv);
         }
         prev_a = acc_a;
         prev_b = acc_b;
