@@ -9,7 +9,9 @@ value        = gradient bytes streamed per second (S*d*4 / step time), GB/s
 roofline     = the dominant kernel against the 8 TB/s HBM peak, algorithmic bytes of one launch /
                its average duration from HIP events on the launch stream inside the timed region:
                the fused step kernel (whole step, S*d*b + 24*d bytes) when the library runs the
-               step as one persistent launch, else the reduce kernel (S*d*b read + 4*d written)
+               step as one persistent launch, else the first kernel of the three-kernel step (the
+               gradient sweep: S*d*b read, plus 4*d written for the mean gradient or, in the
+               streaming kernel, v read and written and w read under weight decay)
 cpu_baseline = the CPU oracle (OpenMP build of the same source) on the host, one step of the
                same workload
 """
@@ -112,7 +114,13 @@ def main() -> int:
     grad_bytes = S * d * b
     total_bytes = grad_bytes + 24 * d
     value = grad_bytes / sec / 1e9
-    reduce_bytes = grad_bytes + 4 * d
+    # first kernel of the three-kernel step: the general reduce kernel reads the gradients and writes
+    # the mean gradient (4 bytes per parameter); the streaming one reads and writes v instead
+    # (8 bytes per parameter) and reads w when there is weight decay (4 more)
+    if path == "streaming":
+        reduce_bytes = grad_bytes + (8 + (4 if wl.weight_decay != 0.0 else 0)) * d
+    else:
+        reduce_bytes = grad_bytes + 4 * d
     roof = None
     if fused:
         ach = total_bytes / (dev_ms * 1e-3) / 1e9
@@ -134,8 +142,10 @@ def main() -> int:
         roof = {"bound": "hbm", "kernel": kname, "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "bytes_per_launch": reduce_bytes, "avg_ms": round(kernel_ms[0], 5),
-                "other_kernels_ms": {"k_scalars": round(kernel_ms[1], 5), "k_update": round(kernel_ms[2], 5)},
-                "update_GBps": round(20 * d / (kernel_ms[2] * 1e-3) / 1e9, 1) if kernel_ms[2] else None}
+                "other_kernels_ms": {"k_scalars": round(kernel_ms[1], 5),
+                                     ("k_apply" if path == "streaming" else "k_update"): round(kernel_ms[2], 5)},
+                "update_GBps": round((12 if path == "streaming" else 20) * d / (kernel_ms[2] * 1e-3) / 1e9, 1)
+                if kernel_ms[2] else None}
 
     cpu = None
     if not args.no_cpu_baseline:
