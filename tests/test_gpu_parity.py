@@ -357,6 +357,41 @@ def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, step_path):
     H.assert_report(H.run_teacher_forced(wl, log=log))
 
 
+def _random_case(seed):
+    rng = np.random.default_rng(seed)
+    sizes = []
+    for _ in range(int(rng.integers(1, 9))):
+        kind = rng.integers(0, 6)
+        if kind == 0:
+            sizes.append(int(rng.integers(0, 4)))                                  # empty or tiny
+        elif kind == 1:
+            sizes.append(int(rng.integers(1, 5000)))
+        elif kind == 2:
+            sizes.append(int(2048 * rng.integers(1, 40) + rng.integers(-3, 4)))   # around whole tiles
+        elif kind == 3:
+            sizes.append(int(rng.integers(100_000, 600_000)))
+        else:
+            sizes.append(int(1024 * rng.integers(1, 64)))
+    S = int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 20, 24, 31, 32, 33, 48, 64, 72, 80]))
+    dtype = int(rng.integers(0, 2))
+    flags = int(rng.choice([0, 0, LAGGED_R, EST_NORM_RATIO, LAGGED_R | EST_NORM_RATIO]))
+    wl = W.custom([(n,) for n in sizes], S, grad_dtype=dtype, momentum=float(rng.choice([0.0, 0.9, 0.99])),
+                  weight_decay=float(rng.choice([0.0, 1e-4, 1e-2])), theta=float(rng.choice([-1.0, 0.0, 0.5, 0.9])),
+                  lr_table=W.lr_step_decay(float(rng.choice([0.01, 0.1])), 16), steps=3, seed=int(seed),
+                  recipe=str(rng.choice(["shared_fresh_signal", "decaying_signal", "per_tensor_scale", "zero_mean"])))
+    return wl, flags, int(rng.integers(0, 4))
+
+
+@pytest.mark.parametrize("seed", range(1000, 1016))
+def test_random_shapes_scales_and_flags(seed):
+    """Seeded random parameter lists (empty, tiny, around whole tiles, large), scales, gradient
+    types, estimator flags, hyper-parameters and pointer alignments."""
+    wl, flags, skew = _random_case(seed)
+    log(f"seed {seed}: numel={wl.numel} S={wl.S} dtype={wl.grad_dtype} flags={flags} skew={skew} "
+        f"rho={wl.momentum} lambda={wl.weight_decay} theta={wl.theta} recipe={wl.recipe}")
+    H.assert_report(H.run_teacher_forced(wl, flags=flags, skew_elems=skew, log=log))
+
+
 # ------------------------------------------------------------------------- the five configs
 def test_config1_every_step_teacher_forced_and_free(step_path):
     wl = W.config(1)
