@@ -878,14 +878,22 @@ __device__ __forceinline__ void fused_cold_mean(const ARGS &p, int c, int tid, d
     const int c4 = rem < 4 ? (int)rem : 4;
     typename FGrad<GT>::Acc acc;
     acc.init();
-    for (int i0 = 0; i0 < p.S; i0 += HG) {
-        typename FGrad<GT>::raw x[HG];
+    // nothing overlaps these loads (no double buffering here), so two half-groups go out together
+    // (the pointer rows are padded to an even number of half-groups): a ragged tile costs
+    // ceil(S / (2 HG)) memory latencies
+    auto fetch = [&](typename FGrad<GT>::raw (&x)[HG], int i0) {
 #pragma unroll
         for (int g = 0; g < HG; ++g) {
             gp_cchar gp = (gp_cchar)row[kRowG + i0 + g] + ((first * 4) >> FGrad<GT>::kShift);
             x[g] = c4 == 4 ? FGrad<GT>::load(gp) : FGrad<GT>::load_partial(gp, c4);
         }
-        fused_accumulate<GT, HG, true>(x, i0, p.S, acc);
+    };
+    for (int i0 = 0; i0 < p.S; i0 += 2 * HG) {
+        typename FGrad<GT>::raw x0[HG], x1[HG];
+        fetch(x0, i0);
+        fetch(x1, i0 + HG);
+        fused_accumulate<GT, HG, true>(x0, i0, p.S, acc);
+        fused_accumulate<GT, HG, true>(x1, i0 + HG, p.S, acc);
     }
     AS_GLOBAL float *gb = (AS_GLOBAL float *)row[kRowGbar] + first;
     float o[4];
@@ -1016,7 +1024,8 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
 
     // phase 1
     FUSED_STAMP(0);
-    for (int c = b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, FusedArgs>(p, c, tid, acc_a, acc_b);
+    // ragged tiles go to the workgroups from the top: those are the ones with one full tile less
+    for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, FusedArgs>(p, c, tid, acc_a, acc_b);
     FUSED_STAMP(1);
 
     if (n_valid > 0) {
@@ -1135,7 +1144,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     for (int q = R; q < q_lds_end; ++q)
         fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
     for (int q = q_hbm; q < n_valid; ++q) fused_tile_apply(cx.locate(q), lane_off, eta);
-    for (int c = b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);
+    for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);  // same owner as in phase 1
     FUSED_STAMP(4);
 }
 
