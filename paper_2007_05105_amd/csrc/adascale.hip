@@ -348,6 +348,48 @@ void launch_reduce_update(const adascale_ctx *c, int grid, hipStream_t s, int S,
 #undef LAUNCH
 }
 
+#ifdef ADASCALE_FUSED_TIMING
+// Development builds only: every workgroup of the fused kernel leaves wall-clock stamps of its
+// phases; after 60 launches the host prints their spread, overall and per XCD, once.
+hipError_t fused_timing_hook(adascale_ctx *c, FusedArgs *fa)
+{
+    static unsigned long long *d_timing = nullptr;
+    if (!d_timing) {
+        const hipError_t e = hipMalloc(&d_timing, sizeof(unsigned long long) * 8 * kFMaxGrid);
+        if (e != hipSuccess) return e;
+    }
+    fa->timing = d_timing;
+    if (c->fused_launches != 60) return hipSuccess;
+    std::vector<unsigned long long> h(8 * kFMaxGrid);
+    const hipError_t e = hipMemcpy(h.data(), d_timing, h.size() * 8, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return e;
+    unsigned long long t0 = ~0ULL;
+    for (int i = 0; i < c->f_grid; ++i) t0 = std::min(t0, h[8 * i]);
+    for (int j = 0; j < 8; ++j) {
+        unsigned long long mn = ~0ULL, mx = 0;
+        double sum = 0;
+        for (int i = 0; i < c->f_grid; ++i) {
+            const unsigned long long v = h[8 * i + j] - t0;
+            mn = std::min(mn, v);
+            mx = std::max(mx, v);
+            sum += v;
+        }
+        fprintf(stderr, "stamp %d: min %.2f us  mean %.2f us  max %.2f us\n", j, mn / 100.0, sum / c->f_grid / 100.0, mx / 100.0);
+    }
+    for (int x = 0; x < 8; ++x) {
+        double s2 = 0, s4 = 0;
+        int n = 0;
+        for (int i = x; i < c->f_grid; i += 8) {
+            s2 += h[8 * i + 2] - t0;
+            s4 += (h[8 * i + 4] - h[8 * i + 3]);
+            ++n;
+        }
+        if (n) fprintf(stderr, "xcd %d: phase1 end mean %.2f us, phase2 mean %.2f us\n", x, s2 / n / 100.0, s4 / n / 100.0);
+    }
+    return hipSuccess;
+}
+#endif
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -646,31 +688,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.lambda = (float)c->cfg.weight_decay;
         fa.sc = sa;
 #ifdef ADASCALE_FUSED_TIMING
-        static unsigned long long *d_timing = nullptr;
-        if (!d_timing) HIP_TRY(c, hipMalloc(&d_timing, sizeof(unsigned long long) * 8 * kFMaxGrid));
-        fa.timing = d_timing;
-        if (c->fused_launches == 60) {
-            std::vector<unsigned long long> h(8 * kFMaxGrid);
-            HIP_TRY(c, hipMemcpy(h.data(), d_timing, h.size() * 8, hipMemcpyDeviceToHost));
-            unsigned long long t0 = ~0ULL;
-            for (int i = 0; i < c->f_grid; ++i) t0 = std::min(t0, h[8 * i]);
-            for (int j = 0; j < 8; ++j) {
-                unsigned long long mn = ~0ULL, mx = 0;
-                double sum = 0;
-                for (int i = 0; i < c->f_grid; ++i) {
-                    const unsigned long long v = h[8 * i + j] - t0;
-                    mn = std::min(mn, v); mx = std::max(mx, v); sum += v;
-                }
-                fprintf(stderr, "stamp %d: min %.2f us  mean %.2f us  max %.2f us\n", j, mn / 100.0, sum / c->f_grid / 100.0, mx / 100.0);
-            }
-            for (int x = 0; x < 8; ++x) {
-                double s2 = 0, s4 = 0; int n = 0;
-                for (int i = x; i < c->f_grid; i += 8) { s2 += h[8 * i + 2] - t0; s4 += (h[8 * i + 4] - h[8 * i + 3]); ++n; }
-                fprintf(stderr, "xcd %d: phase1 end mean %.2f us, phase2 mean %.2f us\n", x, s2 / n / 100.0, s4 / n / 100.0);
-            }
-            for (int i = 0; i < 32; ++i) fprintf(stderr, "%.0f ", (h[8 * i + 2] - t0) / 100.0);
-            fprintf(stderr, "\n");
-        }
+        HIP_TRY(c, fused_timing_hook(c, &fa));
 #endif
         void *args[] = {&fa};
         const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
