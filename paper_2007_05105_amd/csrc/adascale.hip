@@ -53,6 +53,12 @@ struct adascale_ctx {
     std::vector<int> tile_prefix;   // [N+1]
     std::vector<int> span_first;    // [n_spans]
     std::vector<size_t> gbar_off;   // element offset of tensor k in the mean-gradient scratch
+    size_t gbar_len = 0;            // its length in elements
+    // The full scratch (d elements) is only allocated once a step needs it: the general step and
+    // the streaming step without momentum.  Otherwise only the ragged last tiles of the tensors
+    // pass through memory, in a scratch of one tile per tensor.
+    float *d_cold_gbar = nullptr;
+    std::vector<unsigned long long> cold_base;  // per tensor: address that tensor's element 0 would have
     long long d = 0;
     int vec = 4, tile = 1024;
     int n_tiles = 0, span_tiles = 2, n_spans = 0, max_blocks = 1 << 30, group = 0;
@@ -253,6 +259,15 @@ int setup_tiles(adascale_ctx *c)
     HIP_TRY(c, hipMalloc(&c->d_ctiles, sizeof(FTile) * std::max<size_t>(nc, 1)));
     if (nt) HIP_TRY(c, hipMemcpy(c->d_ftiles, c->ftiles.data(), sizeof(FTile) * nt, hipMemcpyHostToDevice));
     if (nc) HIP_TRY(c, hipMemcpy(c->d_ctiles, c->ctiles.data(), sizeof(FTile) * nc, hipMemcpyHostToDevice));
+    // scratch for the ragged tiles: tensor k's tile sits at slot j, and the address handed to the
+    // kernels is the one element 0 of the tensor would have if the whole tensor were there
+    HIP_TRY(c, hipMalloc(&c->d_cold_gbar, sizeof(float) * kFTile * std::max<size_t>(nc, 1)));
+    c->cold_base.assign(N, (unsigned long long)(uintptr_t)c->d_cold_gbar);
+    for (size_t j = 0; j < nc; ++j) {
+        const FTile &t = c->ctiles[j];
+        c->cold_base[t.k] = (unsigned long long)(uintptr_t)(c->d_cold_gbar + j * kFTile) -
+                            (unsigned long long)t.local * kFTile * sizeof(float);
+    }
     c->tiles_ok = true;
 
     if (env_int("ADASCALE_STREAM", 1) == 2) return ADASCALE_OK;  // 2 = keep to the plain reduce kernel
@@ -465,6 +480,7 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         c->gbar_off[k] = goff;
         goff += ((size_t)c->numel[k] + 63) / 64 * 64;  // 256-byte aligned starts
     }
+    c->gbar_len = std::max<size_t>(goff, 64);
     c->n_tiles = (int)tiles;
     c->n_spans = (c->n_tiles + c->span_tiles - 1) / c->span_tiles;
     c->span_first.assign(std::max(c->n_spans, 1), 0);
@@ -483,7 +499,6 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         HIP_TRY(c, hipMalloc(&c->d_span_first, sizeof(int) * c->span_first.size()));
         HIP_TRY(c, hipMalloc(&c->d_tile_prefix, sizeof(int) * (N + 1)));
         HIP_TRY(c, hipMalloc(&c->d_numel, sizeof(long long) * std::max(N, 1)));
-        HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * std::max<size_t>(goff, 64)));
         HIP_TRY(c, hipMalloc(&c->d_lr, sizeof(float) * cfg->lr_table_len));
         // partial slots: one per span (reduce kernel), per workgroup (fused step), or per workgroup
         // plus one per pair of 512-lane tiles (streaming reduce kernel)
@@ -530,6 +545,7 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_numel);
     (void)hipFree(c->d_ptrs);
     (void)hipFree(c->d_gbar);
+    (void)hipFree(c->d_cold_gbar);
     (void)hipFree(c->d_lr);
     (void)hipFree(c->d_partials);
     (void)hipFree(c->d_state);
@@ -608,6 +624,13 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     hipStream_t s = (hipStream_t)hip_stream;
     HIP_TRY(c, hipSetDevice(c->cfg.device));
 
+    // the general kernels pass the whole mean gradient through memory
+    const int path = adascale_step_path(c);
+    if (!c->d_gbar && (path == ADASCALE_PATH_GENERAL || (path == ADASCALE_PATH_STREAMING && !c->stream_momentum))) {
+        HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * c->gbar_len));
+        c->table_valid = false;
+    }
+
     // Build the device pointer table [N][3 + S] in a pinned slot; upload only when it changed.
     const int S_pad = padded_scale(c->cfg.grad_dtype, S);
     const int row_len = S_pad + kRowG;
@@ -620,7 +643,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             unsigned long long *row = tab + (size_t)k * row_len;
             row[kRowW] = (unsigned long long)(uintptr_t)w[k];
             row[kRowV] = (unsigned long long)(uintptr_t)mom[k];
-            row[kRowGbar] = (unsigned long long)(uintptr_t)(c->d_gbar + c->gbar_off[k]);
+            row[kRowGbar] = c->d_gbar ? (unsigned long long)(uintptr_t)(c->d_gbar + c->gbar_off[k]) : c->cold_base[k];
             for (int i = 0; i < S_pad; ++i)
                 row[kRowG + i] = (unsigned long long)(uintptr_t)grads[(size_t)std::min(i, S - 1) * N + k];
         }

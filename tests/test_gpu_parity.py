@@ -284,6 +284,35 @@ def test_elastic_scale_changes_at_quarter_and_half_of_the_budget(scales, step_pa
     gpu.close()
 
 
+def test_scale_beyond_every_512_lane_shape_and_back(step_path):
+    """S = 4100 has no fused or streaming instance: the context moves to the general kernels (and
+    only then allocates the full mean-gradient scratch), then back."""
+    shapes = [(2500,), (5,)]
+    wls = {S: W.custom(shapes, S, theta=0.5, weight_decay=1e-3, lr_table=W.lr_constant(0.05, 8), seed=77) for S in (8, 4100)}
+    inp = {S: W.Inputs(wls[S], "cuda:0") for S in wls}
+    first = inp[8]
+    w = W.views(first.w_flat, first.wl.numel, first.offs32)
+    v = W.views(first.v_flat, first.wl.numel, first.offs32)
+    w64 = [x.cpu().numpy().astype(np.float64) for x in w]
+    v64 = [x.cpu().numpy().astype(np.float64) for x in v]
+    gpu, orc = H.make_gpu(wls[8]), H.make_oracle(wls[8])
+    paths = []
+    for t, S in enumerate([8, 8, 4100, 4100, 8]):
+        if gpu.S != S:
+            gpu.set_scale(S, 0.5)
+            orc.set_scale(S, 0.5)
+        paths.append(gpu.step_path())
+        inp[S].fill_grads(t)
+        gpu.step(w, v, inp[S].g)
+        ost = orc.step(w64, v64, H.grads_to_numpy(inp[S]))
+        rel = H.compare_step(gpu.get_state(), ost, S)
+        assert max(rel[k] for k in ("sigma2_hat", "mu2_hat", "r", "tau", "lr_eff")) <= H.TOL_SCALAR, (t, S, rel)
+    assert paths[2] == paths[3] == "general"
+    assert paths[0] == paths[4] == {"fused": "fused", "three_kernel": "streaming", "general": "general"}[step_path]
+    assert H.tensor_err(first.w_flat, w64, w64, first.wl.numel, first.offs32) <= 1e-5
+    gpu.close()
+
+
 def test_error_paths_launch_nothing():
     """Bad arguments come back as codes; the pointer check refuses host memory and short buffers."""
     with pytest.raises(AdaScaleError) as e:
