@@ -61,3 +61,12 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "library_path", lambda: str(tmp_path / "libadascale.so"))
     with pytest.raises(ImportError):
         binding.load_library()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build is for one GPU: bench.py says so and exits before touching any device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
