@@ -97,8 +97,9 @@ typedef struct {
 /*
  * Create a context for a fixed parameter list (Algorithm 2's inputs S, lr, T_SI plus rho).
  * cfg and the arrays it points to are host memory, read during the call only.  Allocates the
- * device scratch (mean-gradient buffer of d floats, reduction partials, state, lr table) on
- * cfg->device.  On success *out receives the context; on failure *out is NULL.
+ * device scratch (tile tables, reduction partials, state, lr table, a tile per tensor for the
+ * mean gradient of ragged ends) on cfg->device.  On success *out receives the context; on
+ * failure *out is NULL.
  * EINVAL: null cfg/out, S < 1, N < 0, negative numel, unknown dtype or flag, rho outside
  * [0,1), lambda < 0, theta >= 1, L < 1, null numel (N > 0) or lr_table.
  */
@@ -113,7 +114,9 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out);
  * Pointers need only element alignment (16-byte alignment is the fast case).  The host arrays
  * are copied before the call returns; the device tensors must stay valid, and the gradients
  * unmodified, until the stream work completes.  Never blocks on the device except when more
- * than a few distinct pointer sets are in flight at once.  A tensor with numel 0 may have
+ * than a few distinct pointer sets are in flight at once, and allocates nothing except the
+ * first time a context takes the general kernels (see adascale_step_path), which pass the whole
+ * mean gradient through a scratch of d floats.  A tensor with numel 0 may have
  * null pointers.  EINVAL on a null required pointer, or (unless NO_POINTER_CHECK) a pointer
  * that is not device memory of sufficient extent; nothing is launched in that case.
  */
