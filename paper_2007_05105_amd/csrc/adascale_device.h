@@ -588,10 +588,10 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
 //
 // Tiles here are 512 lanes x 4 elements.  Tiles that lie wholly inside a tensor ("full") take
 // the hot path: straight-line code without per-lane predicates.  Slot q of workgroup b is full
-// tile q * gridDim.x + b; slots [0, R) live in VGPRs (R up to 44), the next lds_tiles slots in LDS, and any
-// further slots go through the HBM scratch like in the three-kernel step.  The ragged last tile
-// of each tensor ("cold", at most one per tensor) takes a simple predicated path through the
-// HBM scratch.
+// tile q * gridDim.x + b; slots [0, R) live in VGPRs (R up to 44), the next lds_tiles slots in
+// LDS; for any further slots the sweep leaves the new momentum in v (it does not depend on
+// eta_t) and phase 2 only applies it.  The ragged last tile of each tensor ("cold", at most one
+// per tensor) takes a simple predicated path through a small HBM scratch.
 constexpr int kFThreads = 512;                 // 8 waves: 2 per SIMD, up to 256 VGPRs each
 constexpr int kFWaves = kFThreads / kWave;
 constexpr int kFRegTiles = 44;                 // most f4 per lane kept in VGPRs (176 of the 256 registers)
@@ -954,7 +954,7 @@ __device__ __forceinline__ void fused_cold_update(const FusedArgs &p, int c, int
 // The full-tile slots of one workgroup (wave-uniform).  Slot q holds full tile q * G + b; the
 // workgroup's slots [0, n_valid) exist.  Slots [0, R) are kept in VGPRs (the host picks R so that
 // every workgroup has at least R tiles: that part is straight-line code without branches),
-// [R, q_hbm) in LDS, [q_hbm, n_valid) go through the HBM scratch.
+// [R, q_hbm) in LDS; for [q_hbm, n_valid) nothing is kept (the momentum is updated in the sweep).
 template <int R>
 struct FCtx {
     const FusedArgs &p;

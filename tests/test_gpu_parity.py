@@ -60,7 +60,8 @@ def test_small_multi_tensor_all_scales(S, dtype):
                                      (1, BF16), (4, BF16), (6, BF16), (16, BF16), (27, BF16), (32, BF16), (51, BF16), (64, BF16),
                                      (65, BF16), (130, BF16)])
 def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, dtype, step_path, monkeypatch):
-    """Two workgroups only, so most tiles overflow registers + LDS and go through the HBM scratch."""
+    """Two workgroups only, so most tiles overflow registers + LDS: their sweep updates the
+    momentum in place and phase 2 only applies it."""
     if step_path != "fused":
         pytest.skip("fused step only")
     monkeypatch.setenv("ADASCALE_FUSED_GRID", "2")
