@@ -795,10 +795,10 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
     }
     acc_a += acc.a;
     acc_b += b;
-    // The sums are brought up to date here: left free, the compiler postpones the squares of the
-    // means of every retained tile to the end of phase 1 and keeps their fp64 values alive until
-    // then (8 more registers per retained tile).
-    asm volatile("" : "+v"(acc_a), "+v"(acc_b));
+    // The sums are brought up to date and the means rounded to fp32 here: left free, the compiler
+    // postpones the squares of the means of every retained tile, or their rounding, to the end of
+    // phase 1 and keeps their fp64 values alive until then (8 more registers per retained tile).
+    asm volatile("" : "+v"(acc_a), "+v"(acc_b), "+v"(o[0]), "+v"(o[1]), "+v"(o[2]), "+v"(o[3]));
     // Keep the 8 waves of the workgroup on the same tile: left alone, the older waves win the
     // arbitration for the memory pipeline and the workgroup then waits for its youngest wave.
     if constexpr (std::is_same<HOOK, NoHook>::value) __builtin_amdgcn_s_barrier();
