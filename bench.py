@@ -8,7 +8,7 @@ parameters in 161 tensors (bottleneck-CNN-like shapes), S = 16 fp32 gradient buf
 value        = gradient bytes streamed per second (S*d*4 / step time), GB/s
 roofline     = the dominant kernel against the 8 TB/s HBM peak, algorithmic bytes of one launch /
                its average duration from HIP events on the launch stream inside the timed region:
-               the fused step kernel (whole step, S*d*b + 24*d bytes) when the library runs the
+               the fused step kernel (whole step, S*d*b + 24*d bytes, 20*d without weight decay) when the library runs the
                step as one persistent launch, else the first kernel of the three-kernel step (the
                gradient sweep: S*d*b read, plus 4*d written for the mean gradient or, in the
                streaming kernel, v read and written and w read under weight decay)
@@ -112,7 +112,9 @@ def main() -> int:
 
     d, S, b = wl.d, wl.S, wl.grad_bytes
     grad_bytes = S * d * b
-    total_bytes = grad_bytes + 24 * d
+    # per parameter: 24 bytes (mean gradient or new momentum out and in, w and v in and out); without
+    # weight decay the first sweep need not read w, which leaves 20
+    total_bytes = grad_bytes + (24 if wl.weight_decay != 0.0 else 20) * d
     value = grad_bytes / sec / 1e9
     # first kernel of the three-kernel step: the general reduce kernel reads the gradients and writes
     # the mean gradient (4 bytes per parameter); the streaming one reads and writes v instead

@@ -152,7 +152,9 @@ void adascale_destroy(adascale_ctx *ctx);
 const char *adascale_last_error(const adascale_ctx *ctx);
 
 /* Algorithmic bytes one step moves for this context: S*d*b gradient bytes read once plus the
- * per-parameter traffic of the mean gradient, w and v.  For benchmarks; host only. */
+ * per-parameter traffic of a two-sweep step that keeps nothing on chip: 24 bytes (the new momentum
+ * written and read back, v read, w read twice and written), 20 without weight decay, where the
+ * first sweep does not need w.  For benchmarks; host only. */
 int64_t adascale_step_bytes(const adascale_ctx *ctx);
 
 /*

@@ -416,7 +416,7 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
 {
     if (!c) return 0;
     const int64_t b = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
-    return (int64_t)c->cfg.S * c->d * b + 24 * c->d;
+    return (int64_t)c->cfg.S * c->d * b + (c->cfg.weight_decay != 0.0 ? 24 : 20) * c->d;
 }
 
 int adascale_step_path(const adascale_ctx *c)
