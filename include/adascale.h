@@ -16,7 +16,8 @@
  *
  * Everything runs in the library's own HIP kernels on the caller's stream; no call except
  * adascale_get_state waits for the device.  All functions return an ADASCALE_* code and
- * never throw, abort or print.  A context belongs to one device; calls on one context must
+ * never throw, abort or print.  A context belongs to one device (each call makes it current while
+ * it runs and leaves the caller's current device as it found it); calls on one context must
  * be issued in order on one stream at a time (the context owns scratch that consecutive
  * steps reuse), different contexts are independent.
  */
@@ -162,7 +163,7 @@ int64_t adascale_step_bytes(const adascale_ctx *ctx);
  * (the choice depends on the gradient type, the scale of the moment and the size of the
  * parameter list, and can be steered with the environment for tests and measurements):
  *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient on chip as far
- *                            as it fits (S <= 4096 and at least about a seventh of the mean
+ *                            as it fits (S <= 4096 and at least a fifth of the mean
  *                            gradient fitting in registers + LDS);
  *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
  *                            sweep in memory order: S <= 4096, parameter lists far larger than

@@ -122,6 +122,24 @@ int fail(adascale_ctx *c, int code, const char *fmt, ...)
         if (e_ != hipSuccess) return fail(ctx, ADASCALE_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
     } while (0)
 
+// Makes the context's device current for the duration of a call and puts the caller's back.
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    hipError_t enter(int device)
+    {
+        hipError_t e = hipGetDevice(&prev);
+        if (e != hipSuccess || prev == device) return e;
+        e = hipSetDevice(device);
+        switched = e == hipSuccess;
+        return e;
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
 int env_int(const char *name, int dflt)
 {
     const char *s = getenv(name);
@@ -491,11 +509,12 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
     }
 
     int rc = ADASCALE_OK;
+    DeviceGuard guard;
     auto body = [&]() -> int {
         int ndev = 0;
         HIP_TRY(c, hipGetDeviceCount(&ndev));
         if (cfg->device < 0 || cfg->device >= ndev) return fail(c, ADASCALE_EINVAL, "no such device");
-        HIP_TRY(c, hipSetDevice(cfg->device));
+        HIP_TRY(c, guard.enter(cfg->device));
         HIP_TRY(c, hipMalloc(&c->d_span_first, sizeof(int) * c->span_first.size()));
         HIP_TRY(c, hipMalloc(&c->d_tile_prefix, sizeof(int) * (N + 1)));
         HIP_TRY(c, hipMalloc(&c->d_numel, sizeof(long long) * std::max(N, 1)));
@@ -538,7 +557,8 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
 void adascale_destroy(adascale_ctx *c)
 {
     if (!c) return;
-    (void)hipSetDevice(c->cfg.device);
+    DeviceGuard guard;
+    (void)guard.enter(c->cfg.device);
     (void)hipDeviceSynchronize();
     (void)hipFree(c->d_span_first);
     (void)hipFree(c->d_tile_prefix);
@@ -568,7 +588,8 @@ int adascale_set_scale(adascale_ctx *c, int32_t S_new, double theta)
     if (!c) return ADASCALE_EINVAL;
     if (S_new < 1) return fail(c, ADASCALE_EINVAL, "S must be >= 1");
     if (!(theta < 1.0)) return fail(c, ADASCALE_EINVAL, "theta must be < 1");
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
     const int rc = alloc_pointer_tables(c, S_new);
     if (rc != ADASCALE_OK) return rc;
     c->cfg.S = S_new;
@@ -582,7 +603,8 @@ int adascale_set_state(adascale_ctx *c, int64_t step, double tau, double sigma2_
     if (!c) return ADASCALE_EINVAL;
     if (step < 0 || !(tau >= 0.0) || !(sigma2_bar >= 0.0) || !(mu2_bar >= 0.0))
         return fail(c, ADASCALE_EINVAL, "state values must be non-negative");
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
     hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_state + c->cur, (long long)step,
                        tau, sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len);
     HIP_TRY(c, hipGetLastError());
@@ -594,7 +616,8 @@ int adascale_get_state(adascale_ctx *c, adascale_state *out, void *hip_stream)
     if (!c) return ADASCALE_EINVAL;
     if (!out) return fail(c, ADASCALE_EINVAL, "null out");
     hipStream_t s = (hipStream_t)hip_stream;
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
     int *h_fault = reinterpret_cast<int *>(c->h_state + 1);
     HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state + c->cur, sizeof(DevState), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipMemcpyAsync(h_fault, c->d_fault, sizeof(int), hipMemcpyDeviceToHost, s));
@@ -622,7 +645,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     const int S = c->cfg.S;
     if (N > 0 && (!w || !mom || !grads)) return fail(c, ADASCALE_EINVAL, "null pointer array");
     hipStream_t s = (hipStream_t)hip_stream;
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
 
     // the general kernels pass the whole mean gradient through memory
     const int path = adascale_step_path(c);
@@ -828,7 +852,8 @@ int adascale_profile_begin(adascale_ctx *c, int32_t max_steps)
 {
     if (!c) return ADASCALE_EINVAL;
     if (max_steps < 1 || max_steps > 100000) return fail(c, ADASCALE_EINVAL, "max_steps out of range");
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
     while ((int)c->prof_ev.size() < 4 * max_steps) {
         hipEvent_t e;
         HIP_TRY(c, hipEventCreate(&e));
@@ -849,7 +874,8 @@ int adascale_profile_end(adascale_ctx *c, double ms[3], int32_t *n_steps)
     ms[0] = ms[1] = ms[2] = 0.0;
     *n_steps = c->prof_n;
     if (c->prof_n == 0) return ADASCALE_OK;
-    HIP_TRY(c, hipSetDevice(c->cfg.device));
+    DeviceGuard guard;
+    HIP_TRY(c, guard.enter(c->cfg.device));
     HIP_TRY(c, hipEventSynchronize(c->prof_ev[(size_t)4 * (c->prof_n - 1) + 3]));
     for (int i = 0; i < c->prof_n; ++i)
         for (int j = 0; j < 3; ++j) {
