@@ -178,6 +178,17 @@ int adascale_step_path(const adascale_ctx *ctx);
 int adascale_uses_fused_step(const adascale_ctx *ctx);
 
 /*
+ * How the fused and streaming kernels consume the S gradients of a tile (Algorithm 1's sum over
+ * the batches): in shape[1] half-groups of shape[0] loads each, alternating between two register
+ * buffers; the pointer table rows are padded to shape[2] = shape[0] * shape[1] replica slots.
+ * Host only, needs no device.  Returns a bit mask: 1 = the fused step has a kernel instance for
+ * this gradient type and scale (at every register level, both gain variants), 2 = the streaming
+ * reduce kernel has one; 0 (shape untouched) if the scale is outside their range, in which case
+ * the general kernels run.  For tests and diagnostics.
+ */
+int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3]);
+
+/*
  * Benchmark instrumentation: while profiling is on, every adascale_step also records HIP
  * events on its stream before and after each of its kernels (up to max_steps steps).
  * adascale_profile_end waits for the stream work, writes the average duration in

@@ -19,7 +19,7 @@ _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
            "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_bytes",
            "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step",
-           "adascale_step_path"]
+           "adascale_step_path", "adascale_kernel_shape"]
 
 
 class AdaScaleError(RuntimeError):
@@ -85,8 +85,17 @@ def load_library() -> C.CDLL:
         lib.adascale_uses_fused_step.restype = C.c_int
         lib.adascale_step_path.argtypes = [C.c_void_p]
         lib.adascale_step_path.restype = C.c_int
+        lib.adascale_kernel_shape.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+        lib.adascale_kernel_shape.restype = C.c_int
         _lib = lib
     return _lib
+
+
+def kernel_shape(grad_dtype: int, S: int):
+    """adascale_kernel_shape: (mask, (loads per half-group, half-groups, padded replica slots))."""
+    shape = (C.c_int32 * 3)()
+    mask = load_library().adascale_kernel_shape(grad_dtype, S, shape)
+    return mask, tuple(shape)
 
 
 def _ptr_array(tensors: Sequence) -> "C.Array":

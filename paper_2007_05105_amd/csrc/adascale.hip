@@ -446,6 +446,20 @@ int adascale_step_path(const adascale_ctx *c)
     return ADASCALE_PATH_GENERAL;
 }
 
+int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3])
+{
+    int hg = 0, nh = 0;
+    if ((grad_dtype != ADASCALE_F32 && grad_dtype != ADASCALE_BF16) || !shape || !fused_shape(grad_dtype, S, &hg, &nh))
+        return 0;
+    shape[0] = hg;
+    shape[1] = nh;
+    shape[2] = padded_scale(grad_dtype, S);
+    bool fused = true;
+    for (int level = 0; level < kFRegLevels; ++level)
+        for (int lag = 0; lag < 2; ++lag) fused = fused && fused_kernel_for(grad_dtype, S, level, lag != 0) != nullptr;
+    return (fused ? 1 : 0) | (stream_kernel_for(grad_dtype, S) ? 2 : 0);
+}
+
 int adascale_uses_fused_step(const adascale_ctx *c) { return adascale_step_path(c) == ADASCALE_PATH_FUSED ? 1 : 0; }
 
 int adascale_init(const adascale_config *cfg, adascale_ctx **out)

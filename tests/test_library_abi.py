@@ -56,6 +56,30 @@ def test_init_argument_errors_need_no_gpu():
         binding.AdaScale([10], 2, [0.1], momentum=1.5)
 
 
+def test_every_scale_up_to_4096_has_a_kernel_shape_and_instances():
+    """Host logic that picks the kernel instance: the half-groups cover S with less than one pair of
+    half-groups of padding, loads per half-group stay within what the register buffers hold, and an
+    instance exists for every scale in range (outside it the general kernels run)."""
+    if not os.path.exists(binding.library_path()):
+        pytest.skip("libadascale.so not built")
+    for dtype, cap in ((0, 4), (1, 8)):
+        for S in range(1, 4097):
+            mask, (hg, nh, padded) = binding.kernel_shape(dtype, S)
+            assert mask == 3, (dtype, S)
+            assert 1 <= hg <= cap and hg & (hg - 1) == 0
+            assert nh >= 2 and nh % 2 == 0
+            assert padded == hg * nh and S <= padded < S + 2 * hg
+            assert 2 * hg >= min(S, 2 * cap)          # the two buffers together hold S, or are full size
+        for S in (0, -3, 4097, 1 << 20):
+            assert binding.kernel_shape(dtype, S)[0] == 0
+    assert binding.kernel_shape(7, 16)[0] == 0
+    # the shapes the benchmark configurations run with
+    assert binding.kernel_shape(0, 16)[1] == (4, 4, 16)
+    assert binding.kernel_shape(0, 8)[1] == (4, 2, 8)
+    assert binding.kernel_shape(1, 32)[1] == (8, 4, 32)
+    assert binding.kernel_shape(1, 64)[1] == (8, 8, 64)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "library_path", lambda: str(tmp_path / "libadascale.so"))
