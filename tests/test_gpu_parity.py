@@ -83,6 +83,17 @@ def test_element_aligned_pointers(skew, dtype):
     H.assert_report(rep)
 
 
+@pytest.mark.parametrize("S,dtype", [(4, F32), (16, F32), (32, BF16)])
+def test_one_allocation_per_replica(S, dtype):
+    """The S gradient buffers in allocations of their own (the other tests pass rows of one allocation)."""
+    wl = W.custom(SMALL_SHAPES + [(300, 1000)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5,
+                  lr_table=W.lr_step_decay(0.1, 8), steps=3, seed=40 + S)
+    inp = W.Inputs(wl, "cuda:0", one_allocation=False)
+    assert len({g.untyped_storage().data_ptr() for g in inp.g_flat}) == S
+    rep = H.run_teacher_forced(wl, inputs=inp, log=log)
+    H.assert_report(rep)
+
+
 @pytest.mark.parametrize("recipe,S", [("identical", 4), ("zero_mean", 8), ("zeros", 4), ("zeros", 1),
                                       ("identical", 1)])
 def test_degenerate_gradients(recipe, S):

@@ -231,7 +231,10 @@ class Inputs:
     both consumers read the same bits out of these buffers.
     """
 
-    def __init__(self, wl: Workload, device: str | torch.device = "cpu", skew_elems: int = 0):
+    def __init__(self, wl: Workload, device: str | torch.device = "cpu", skew_elems: int = 0,
+                 one_allocation: bool = True):
+        """`one_allocation`: the S gradient buffers are rows of one [S, length] allocation, the
+        layout a gathered set of per-replica gradients has (False: one allocation per replica)."""
         self.wl, self.device = wl, torch.device(device)
         self.offs32, self.len32 = layout(wl.numel, 4, skew_elems=skew_elems)
         self.offs_g, self.len_g = layout(wl.numel, wl.grad_bytes, skew_elems=skew_elems)
@@ -242,8 +245,13 @@ class Inputs:
         for n, o in zip(wl.numel, self.offs32):
             self.w_flat[o:o + n] = tmp[o:o + n]
         del tmp
-        self.g_flat = [torch.zeros(self.len_g, dtype=wl.torch_grad_dtype(), device=dev)
-                       for _ in range(wl.S)]
+        if one_allocation:
+            row = (self.len_g * wl.grad_bytes + _ALIGN_BYTES - 1) // _ALIGN_BYTES * _ALIGN_BYTES // wl.grad_bytes
+            self.g_all = torch.zeros(max(1, wl.S * row), dtype=wl.torch_grad_dtype(), device=dev)
+            self.g_flat = [self.g_all[i * row: i * row + self.len_g] for i in range(wl.S)]
+        else:
+            self.g_flat = [torch.zeros(self.len_g, dtype=wl.torch_grad_dtype(), device=dev)
+                           for _ in range(wl.S)]
         self.w = views(self.w_flat, wl.numel, self.offs32)
         self.v = views(self.v_flat, wl.numel, self.offs32)
         self.g = [views(f, wl.numel, self.offs_g) for f in self.g_flat]
