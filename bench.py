@@ -156,7 +156,7 @@ def main() -> int:
         w64, v64 = H.params_to_numpy64(inp)
         g_np = H.grads_to_numpy(inp)
         reps, c0 = 0, time.perf_counter()
-        while reps < 1 or (time.perf_counter() - c0 < 10.0 and reps < 20):
+        while reps < 1 or (time.perf_counter() - c0 < 10.0 and reps < 400):
             orc.step(w64, v64, g_np)
             reps += 1
         csec = (time.perf_counter() - c0) / reps
