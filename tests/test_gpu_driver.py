@@ -74,3 +74,37 @@ def test_noisy_quadratic_reaches_t_si_at_every_scale():
             assert np.abs(w_gpu - w_or).max() <= 2e-5 * np.abs(w_or).max()
     assert steps[1] == L and steps[1] > steps[4] > steps[16]     # S = 1: r = 1, tau = t
     assert loss[4] <= 1.1 * loss[1] and loss[16] <= 1.1 * loss[1]   # quality does not degrade with scale
+
+
+def test_linear_scaling_baseline_runs_through_a_scale_one_context():
+    """The comparison run of Sec. 4 (linear scaling with warm-up) through the same library: a
+    scale-1 context (gain 1, clock = iteration count) given the LSW table and the mean of the S
+    gradients.  Checks the plumbing -- ceil(T/S) iterations, eta_t = table[t] -- and prints the
+    objective next to AdaScale's; no claim is tested on it."""
+    from paper_2007_05105_amd import schedules as SCH
+    S = 16
+    h, c, lr = problem()
+    table = SCH.lsw_schedule(lr, S)
+    assert len(table) == math.ceil(L / S)
+    w, v = [torch.zeros(D, device="cuda:0")], [torch.zeros(D, device="cuda:0")]
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(100 + S)
+    ada = AdaScale([D], 1, table, momentum=0.9)
+    gbar = [[torch.empty(D, device="cuda:0")]]
+    seen = []
+
+    def make_grads(t):
+        base = h * (w[0] - c)
+        noise = torch.randn(S, D, generator=gen, device="cuda:0").mean(dim=0)
+        gbar[0][0].copy_(base + noise)
+        return gbar
+
+    steps = run_until_done(ada, w, v, make_grads, max_steps=L, on_step=lambda t, st: seen.append((t, st.r, st.tau, st.lr_eff)))
+    ada.close()
+    assert steps == len(table)
+    for t, r, tau, eta in seen:
+        assert r == 1.0 and tau == t and eta == float(table[t - 1])
+    loss_lsw = float(0.5 * torch.sum(h * (w[0] - c) ** 2))
+    _, loss_as, _, _, _ = train(S, with_oracle=False)
+    print("S = 16: LSW objective", loss_lsw, "after", steps, "iterations; AdaScale", loss_as, flush=True)
+    assert math.isfinite(loss_lsw)
