@@ -134,7 +134,10 @@ class AdaScale:
 
     def step(self, w: List, mom: List, grads: List[List], stream=None) -> None:
         """One iteration: w[k], mom[k] fp32 device tensors updated in place; grads[i][k] is
-        replica i's gradient of tensor k.  Asynchronous on `stream` (default: torch's current)."""
+        replica i's gradient of tensor k.  Asynchronous on `stream` (default: torch's current).
+        The pointer arrays are rebuilt only when the tensor objects differ from the last call's;
+        after giving one of them new storage in place (`t.data = ...`, `t.set_()`), call
+        `invalidate()`."""
         if len(grads) != self.S or len(w) != len(self.numel) or len(mom) != len(self.numel):
             raise ValueError("need S gradient lists and N parameter / momentum tensors")
         key = (tuple(id(t) for t in w), tuple(id(t) for t in mom), tuple(id(t) for g in grads for t in g))
@@ -148,6 +151,11 @@ class AdaScale:
             self._cache_key = key
         pw, pm, pg, _ = self._cache
         self._check(self._lib.adascale_step(self._h, pw, pm, pg, C.c_void_p(self._stream(stream))))
+
+    def invalidate(self) -> None:
+        """Forget the cached pointer arrays (see `step`)."""
+        self._cache_key = None
+        self._cache = None
 
     def step_raw(self, pw, pm, pg, stream: int) -> int:
         """adascale_step on prebuilt ctypes pointer arrays; returns the status code."""
