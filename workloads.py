@@ -25,6 +25,7 @@ F32 = 0
 BF16 = 1
 
 _ALIGN_BYTES = 256  # start of every tensor inside a flat buffer (allocator-like)
+_ROW_ALIGN_BYTES = 2 << 20  # start of every replica's row inside the one gradient allocation
 
 
 # --------------------------------------------------------------------------- shapes
@@ -246,7 +247,10 @@ class Inputs:
             self.w_flat[o:o + n] = tmp[o:o + n]
         del tmp
         if one_allocation:
-            row = (self.len_g * wl.grad_bytes + _ALIGN_BYTES - 1) // _ALIGN_BYTES * _ALIGN_BYTES // wl.grad_bytes
+            # rows start on 2 MiB boundaries once they are that long (256 bytes for the small shapes)
+            nbytes = self.len_g * wl.grad_bytes
+            a = _ROW_ALIGN_BYTES if nbytes >= _ROW_ALIGN_BYTES else _ALIGN_BYTES
+            row = (nbytes + a - 1) // a * a // wl.grad_bytes
             self.g_all = torch.zeros(max(1, wl.S * row), dtype=wl.torch_grad_dtype(), device=dev)
             self.g_flat = [self.g_all[i * row: i * row + self.len_g] for i in range(wl.S)]
         else:
