@@ -189,6 +189,28 @@ int adascale_uses_fused_step(const adascale_ctx *ctx);
 int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3]);
 
 /*
+ * What adascale_init would decide for cfg's parameter list, gradient type, scale and flags on a
+ * device with `compute_units` compute units and `lds_bytes` of LDS per workgroup (MI355X: 256 and
+ * 163840): how the list splits into whole 512-lane tiles (2048 elements, inside one tensor) and
+ * ragged last tiles, the grids, how many tiles of the mean gradient each workgroup of the fused
+ * step keeps in registers and in LDS, and the path.  Host only: no device is touched, cfg's
+ * lr_table, device and the optimizer constants are not read.  The fields of a path that does not
+ * apply are 0.  (adascale_init additionally asks the runtime whether the fused grid can be
+ * resident at once; on MI355X it can.)  For tests and diagnostics.
+ */
+typedef struct {
+    int64_t full_tiles, ragged_tiles;
+    int32_t path;                 /* ADASCALE_PATH_* */
+    int32_t fused_grid;           /* workgroups of the fused step, one per compute unit at most */
+    int32_t tiles_per_workgroup;  /* whole tiles per workgroup, rounded up */
+    int32_t register_tiles;       /* of those, kept in registers ... */
+    int32_t lds_tiles;            /* ... and in LDS; the rest passes through memory */
+    int32_t on_chip_percent;
+    int32_t stream_grid;          /* workgroups of the streaming reduce kernel */
+} adascale_plan_info;
+int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds_bytes, adascale_plan_info *out);
+
+/*
  * Benchmark instrumentation: while profiling is on, every adascale_step also records HIP
  * events on its stream before and after each of its kernels (up to max_steps steps).
  * adascale_profile_end waits for the stream work, writes the average duration in

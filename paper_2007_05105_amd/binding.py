@@ -19,7 +19,7 @@ _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
            "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_bytes",
            "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step",
-           "adascale_step_path", "adascale_kernel_shape"]
+           "adascale_step_path", "adascale_kernel_shape", "adascale_plan"]
 
 
 class AdaScaleError(RuntimeError):
@@ -40,6 +40,15 @@ class State(C.Structure):
                 ("sum_sq", C.c_double), ("sq_mean", C.c_double), ("sigma2_hat", C.c_double),
                 ("mu2_hat", C.c_double), ("sigma2_bar", C.c_double), ("mu2_bar", C.c_double),
                 ("done", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class PlanInfo(C.Structure):
+    _fields_ = [("full_tiles", C.c_int64), ("ragged_tiles", C.c_int64), ("path", C.c_int32),
+                ("fused_grid", C.c_int32), ("tiles_per_workgroup", C.c_int32), ("register_tiles", C.c_int32),
+                ("lds_tiles", C.c_int32), ("on_chip_percent", C.c_int32), ("stream_grid", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -87,6 +96,8 @@ def load_library() -> C.CDLL:
         lib.adascale_step_path.restype = C.c_int
         lib.adascale_kernel_shape.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         lib.adascale_kernel_shape.restype = C.c_int
+        lib.adascale_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int64, C.POINTER(PlanInfo)]
+        lib.adascale_plan.restype = C.c_int
         _lib = lib
     return _lib
 
@@ -96,6 +107,22 @@ def kernel_shape(grad_dtype: int, S: int):
     shape = (C.c_int32 * 3)()
     mask = load_library().adascale_kernel_shape(grad_dtype, S, shape)
     return mask, tuple(shape)
+
+
+def plan(numel: Sequence[int], S: int, grad_dtype: int = F32, flags: int = 0, compute_units: int = 256,
+         lds_bytes: int = 160 * 1024) -> dict:
+    """adascale_plan: what adascale_init would decide for this parameter list on a device with the
+    given compute units and LDS per workgroup (defaults: MI355X); needs no device."""
+    lib = load_library()
+    n = (C.c_int64 * len(numel))(*[int(x) for x in numel])
+    cfg = Config(S, len(numel), n, grad_dtype, 0.0, 0.0, -1.0, 0.0, None, 0, 0, flags)
+    info = PlanInfo()
+    rc = lib.adascale_plan(C.byref(cfg), compute_units, lds_bytes, C.byref(info))
+    if rc != 0:
+        raise AdaScaleError(rc, lib.adascale_last_error(None).decode())
+    d = info.as_dict()
+    d["path"] = ("general", "fused", "streaming")[d["path"]]
+    return d
 
 
 def _ptr_array(tensors: Sequence) -> "C.Array":

@@ -253,6 +253,65 @@ const void *stream_kernel_for(int dtype, int S)
 constexpr size_t kStreamLdsPad = 96 * 1024;
 constexpr int kFusedMinPct = 20;  // least share of the mean gradient on chip for the fused step
 
+// ---- planning: pure host arithmetic (no HIP calls), shared by the set-up below and adascale_plan ----
+
+// Whole 512-lane tiles (inside one tensor) and ragged last tiles of a parameter list; false if the
+// list is outside what the 512-lane kernels index (then the general kernels run).
+bool plan_tiles(const long long *numel, int N, long long *full, long long *ragged)
+{
+    long long nt = 0, nc = 0;
+    for (int k = 0; k < N; ++k) {
+        if (numel[k] >= (1LL << 40)) return false;
+        nt += numel[k] / kFTile;
+        if (nt > 0x3fffffffLL) return false;
+        if (numel[k] % kFTile) ++nc;
+    }
+    *full = nt;
+    *ragged = nc;
+    return true;
+}
+
+// May the streaming reduce kernel run on this device at all (its grid: plan_stream_grid)?
+bool plan_stream_ok(size_t lds_per_workgroup)
+{
+    if (env_int("ADASCALE_STREAM", 1) == 2) return false;  // 2 = keep to the plain reduce kernel
+    return lds_per_workgroup >= kStreamLdsPad + 1024;
+}
+
+int plan_stream_grid(long long nt, long long nc, int cus)
+{
+    const long long n_pairs = (nt + 1) / 2;
+    return (int)std::max<long long>(1, std::min<long long>(std::max<long long>(n_pairs, nc), std::min(cus, kFMaxGrid)));
+}
+
+// The fused step's shape for a parameter list on a device with `cus` compute units and
+// `lds_per_workgroup` bytes of LDS: grid (one workgroup per CU), tiles per workgroup, the
+// register-slot level, the LDS capacity in tiles, the share of the mean gradient kept on chip.
+struct FusedPlan {
+    bool ok = false;
+    int grid = 0, tpb = 0, level = 0, lds_cap = 0, on_chip_pct = 0;
+};
+
+FusedPlan plan_fused(long long nt, long long nc, int cus_of_device, size_t lds_per_workgroup, bool stream_ok)
+{
+    FusedPlan f;
+    if (env_int("ADASCALE_FUSED", 1) == 2) return f;  // 2 = force the three-kernel step
+    if (nt + nc == 0) return f;
+    const int cus = std::min(std::min(cus_of_device, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
+    f.grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
+    f.tpb = (int)((nt + f.grid - 1) / f.grid);
+    // register-slot level: the highest whose slot count every workgroup can fill
+    for (int l = 0; l < kFRegLevels; ++l)
+        if (fused_regs_at(l) <= nt / f.grid) f.level = l;
+    f.lds_cap = lds_per_workgroup > 6144 ? (int)((lds_per_workgroup - 6144) / (kFThreads * sizeof(f4))) : 0;  // static LDS is ~4.2 KB
+    // with little of the mean gradient on chip the three-kernel step with the streaming reduce
+    // kernel is the faster one (measured crossover: 13-25 % on chip, depending on S and gradient type)
+    f.on_chip_pct = f.tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(f.level) + std::min(f.tpb, f.lds_cap)) / f.tpb);
+    if (stream_ok && f.on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return f;
+    f.ok = true;
+    return f;
+}
+
 // Tile tables of the 512-lane kernels: whole tiles (inside one tensor) and the ragged last tile
 // of each tensor; the streaming reduce kernel's grid and counters.
 int setup_tiles(adascale_ctx *c)
@@ -263,12 +322,12 @@ int setup_tiles(adascale_ctx *c)
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
     c->n_cus = prop.multiProcessorCount;
     const int N = (int)c->numel.size();
+    long long full = 0, ragged = 0;
+    if (!plan_tiles(c->numel.data(), N, &full, &ragged)) return ADASCALE_OK;
     c->ftiles.clear();
     c->ctiles.clear();
     for (int k = 0; k < N; ++k) {
-        if (c->numel[k] >= (1LL << 40)) return ADASCALE_OK;
         const long long nf = c->numel[k] / kFTile;
-        if ((long long)c->ftiles.size() + nf > 0x3fffffffLL) return ADASCALE_OK;
         for (long long j = 0; j < nf; ++j) c->ftiles.push_back(FTile{k, (int)j});
         if (c->numel[k] % kFTile) c->ctiles.push_back(FTile{k, (int)nf});
     }
@@ -288,11 +347,8 @@ int setup_tiles(adascale_ctx *c)
     }
     c->tiles_ok = true;
 
-    if (env_int("ADASCALE_STREAM", 1) == 2) return ADASCALE_OK;  // 2 = keep to the plain reduce kernel
-    if (prop.sharedMemPerBlock < kStreamLdsPad + 1024) return ADASCALE_OK;
-    const long long n_pairs = ((long long)nt + 1) / 2;
-    c->s_grid = (int)std::max<long long>(1, std::min<long long>(std::max<long long>(n_pairs, (long long)nc),
-                                                               std::min(c->n_cus, kFMaxGrid)));
+    if (!plan_stream_ok(prop.sharedMemPerBlock)) return ADASCALE_OK;
+    c->s_grid = plan_stream_grid((long long)nt, (long long)nc, c->n_cus);
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
         const void *fn = stream_kernel_for(c->cfg.grad_dtype, S);
@@ -305,43 +361,33 @@ int setup_tiles(adascale_ctx *c)
     return ADASCALE_OK;
 }
 
-// Decide whether the fused single-launch step applies: the grid (one workgroup per CU), tiles
-// per workgroup, the LDS capacity in tiles and the register-slot level.  Which instance runs is
-// looked up per step from the scale of the moment (it may change between steps).
+// Decide whether the fused single-launch step applies (plan_fused) and prepare its kernel
+// instances.  Which instance runs is looked up per step from the scale of the moment (it may
+// change between steps).
 int setup_fused(adascale_ctx *c)
 {
     c->fused_ok = false;
-    if (env_int("ADASCALE_FUSED", 1) == 2) return ADASCALE_OK;              // 2 = force the three-kernel step
     if (!c->tiles_ok) return ADASCALE_OK;
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
     if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
-    const long long nt = (long long)c->ftiles.size(), nc = (long long)c->ctiles.size();
-    const int cus = std::min(std::min(prop.multiProcessorCount, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
-    const int grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
-    const int tpb = (int)((nt + grid - 1) / grid);
-    int level = 0;  // register-slot level: the highest whose (largest) slot count every workgroup can fill
-    for (int l = 0; l < kFRegLevels; ++l)
-        if (fused_regs_at(l) <= nt / grid) level = l;
-    const int lds_cap = (int)((prop.sharedMemPerBlock - 6144) / (kFThreads * sizeof(f4)));  // static LDS is ~4.2 KB
-    // with little of the mean gradient on chip the three-kernel step with the streaming reduce
-    // kernel is the faster one (measured crossover: 13-25 % on chip, depending on S and gradient type)
-    const int on_chip_pct = tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(level) + std::min(tpb, lds_cap)) / tpb);
-    if (c->stream_ok && on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return ADASCALE_OK;
-    const size_t lds_bytes = (size_t)lds_cap * kFThreads * sizeof(f4);
+    const FusedPlan f = plan_fused((long long)c->ftiles.size(), (long long)c->ctiles.size(), prop.multiProcessorCount,
+                                   prop.sharedMemPerBlock, c->stream_ok);
+    if (!f.ok) return ADASCALE_OK;
+    const size_t lds_bytes = (size_t)f.lds_cap * kFThreads * sizeof(f4);
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
-        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
+        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, f.level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
         if (!fn) continue;
         HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
         int per_cu = 0;
         HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
-        if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < grid) return ADASCALE_OK;
+        if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < f.grid) return ADASCALE_OK;
     }
-    c->f_grid = grid;
-    c->f_tpb = tpb;
-    c->f_lds_cap = lds_cap;
-    c->f_level = level;
+    c->f_grid = f.grid;
+    c->f_tpb = f.tpb;
+    c->f_lds_cap = f.lds_cap;
+    c->f_level = f.level;
     c->fused_ok = true;
     return ADASCALE_OK;
 }
@@ -458,6 +504,39 @@ int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3])
     for (int level = 0; level < kFRegLevels; ++level)
         for (int lag = 0; lag < 2; ++lag) fused = fused && fused_kernel_for(grad_dtype, S, level, lag != 0) != nullptr;
     return (fused ? 1 : 0) | (stream_kernel_for(grad_dtype, S) ? 2 : 0);
+}
+
+int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds_bytes, adascale_plan_info *out)
+{
+    if (!cfg || !out || cfg->S < 1 || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && !cfg->numel) || compute_units < 1 ||
+        lds_bytes < 0 || (cfg->grad_dtype != ADASCALE_F32 && cfg->grad_dtype != ADASCALE_BF16))
+        return fail(nullptr, ADASCALE_EINVAL, "bad argument to adascale_plan");
+    for (int k = 0; k < cfg->n_tensors; ++k)
+        if (cfg->numel[k] < 0) return fail(nullptr, ADASCALE_EINVAL, "negative numel");
+    *out = adascale_plan_info{};
+    std::vector<long long> numel(cfg->numel, cfg->numel + cfg->n_tensors);
+    long long d = 0;
+    for (long long n : numel) d += n;
+    long long full = 0, ragged = 0;
+    const bool tiles_ok = d > 0 && plan_tiles(numel.data(), cfg->n_tensors, &full, &ragged);
+    out->path = ADASCALE_PATH_GENERAL;
+    if (!tiles_ok) return ADASCALE_OK;
+    out->full_tiles = full;
+    out->ragged_tiles = ragged;
+    const bool stream_ok = plan_stream_ok((size_t)lds_bytes);
+    if (stream_ok) out->stream_grid = plan_stream_grid(full, ragged, compute_units);
+    const FusedPlan f = plan_fused(full, ragged, compute_units, (size_t)lds_bytes, stream_ok);
+    const bool lag = (cfg->flags & ADASCALE_LAGGED_R) != 0;
+    if (f.ok) {
+        out->fused_grid = f.grid;
+        out->tiles_per_workgroup = f.tpb;
+        out->register_tiles = fused_regs_at(f.level);
+        out->lds_tiles = std::max(0, std::min(f.tpb - fused_regs_at(f.level), f.lds_cap));
+        out->on_chip_percent = f.on_chip_pct;
+    }
+    if (f.ok && fused_kernel_for(cfg->grad_dtype, cfg->S, f.level, lag)) out->path = ADASCALE_PATH_FUSED;
+    else if (stream_ok && stream_kernel_for(cfg->grad_dtype, cfg->S)) out->path = ADASCALE_PATH_STREAMING;
+    return ADASCALE_OK;
 }
 
 int adascale_uses_fused_step(const adascale_ctx *c) { return adascale_step_path(c) == ADASCALE_PATH_FUSED ? 1 : 0; }

@@ -34,8 +34,11 @@ def test_struct_layouts_match_header(tmp_path):
     src = tmp_path / "layout.c"
     fields_c = [n for n, _ in binding.Config._fields_]
     fields_s = [n for n, _ in binding.State._fields_]
+    fields_p = [n for n, _ in binding.PlanInfo._fields_]
     body = "".join(f'printf("%zu\\n", offsetof(adascale_config, {f}));' for f in fields_c)
     body += "".join(f'printf("%zu\\n", offsetof(adascale_state, {f}));' for f in fields_s)
+    body += "".join(f'printf("%zu\\n", offsetof(adascale_plan_info, {f}));' for f in fields_p)
+    body += 'printf("%zu\\n", sizeof(adascale_plan_info));'
     src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "adascale.h"\nint main(void){'
                    'printf("%zu\\n%zu\\n", sizeof(adascale_config), sizeof(adascale_state));' + body + "return 0;}")
     exe = tmp_path / "layout"
@@ -43,6 +46,7 @@ def test_struct_layouts_match_header(tmp_path):
     out = [int(x) for x in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
     assert out[0] == C.sizeof(binding.Config) and out[1] == C.sizeof(binding.State)
     got = [getattr(binding.Config, f).offset for f in fields_c] + [getattr(binding.State, f).offset for f in fields_s]
+    got += [getattr(binding.PlanInfo, f).offset for f in fields_p] + [C.sizeof(binding.PlanInfo)]
     assert out[2:] == got
 
 
@@ -78,6 +82,55 @@ def test_every_scale_up_to_4096_has_a_kernel_shape_and_instances():
     assert binding.kernel_shape(0, 8)[1] == (4, 2, 8)
     assert binding.kernel_shape(1, 32)[1] == (8, 4, 32)
     assert binding.kernel_shape(1, 64)[1] == (8, 8, 64)
+
+
+def test_plan_of_the_benchmark_configurations(monkeypatch):
+    """Host logic that lays a parameter list out over the chip (no device needed): tile counts
+    against a count in Python, the split of the mean gradient between registers, LDS and memory,
+    and the path, for the five workloads on an MI355X-sized device."""
+    if not os.path.exists(binding.library_path()):
+        pytest.skip("libadascale.so not built")
+    import workloads as W
+    for name in ("ADASCALE_FUSED", "ADASCALE_STREAM", "ADASCALE_FUSED_MIN_PCT", "ADASCALE_FUSED_GRID"):
+        monkeypatch.delenv(name, raising=False)
+    expect = {1: "fused", 2: "fused", 3: "fused", 4: "fused", 5: "streaming"}
+    for cfg in range(1, 6):
+        wl = W.config(cfg)
+        p = binding.plan(wl.numel, wl.S, wl.grad_dtype)
+        full = sum(n // 2048 for n in wl.numel)
+        ragged = sum(1 for n in wl.numel if n % 2048)
+        assert (p["full_tiles"], p["ragged_tiles"]) == (full, ragged)
+        assert p["path"] == expect[cfg], (cfg, p)
+        assert p["stream_grid"] == min(256, max((full + 1) // 2, ragged, 1))
+        if p["path"] == "fused":
+            g = p["fused_grid"]
+            assert g == min(256, max(full, ragged)) and p["tiles_per_workgroup"] == -(-full // g)
+            assert p["register_tiles"] in (0, 10, 30, 44) and p["register_tiles"] <= full // g   # every workgroup fills them
+            assert p["register_tiles"] + p["lds_tiles"] <= p["tiles_per_workgroup"]
+            assert 0 <= p["lds_tiles"] <= 19                                                   # 19 tiles of 8 KB fit beside the static LDS
+            kept = min(p["tiles_per_workgroup"], p["register_tiles"] + p["lds_tiles"])
+            assert p["on_chip_percent"] == min(100, 100 * kept // p["tiles_per_workgroup"]) >= 20
+    p3, p4 = binding.plan(W.config(3).numel, 16), binding.plan(W.config(4).numel, 32, binding.BF16)
+    assert (p3["register_tiles"], p3["on_chip_percent"]) == (44, 100)
+    assert (p4["register_tiles"], p4["lds_tiles"], p4["tiles_per_workgroup"], p4["on_chip_percent"]) == (44, 19, 116, 54)
+    # scales beyond the 512-lane kernels' range, an empty list, and the environment switches
+    assert binding.plan(W.config(3).numel, 5000)["path"] == "general"
+    assert binding.plan([], 4) == dict(binding.plan([0, 0], 4), path="general")
+    assert binding.plan([7], 4)["ragged_tiles"] == 1 and binding.plan([7], 4)["fused_grid"] == 1
+    monkeypatch.setenv("ADASCALE_FUSED", "2")
+    assert binding.plan(W.config(3).numel, 16)["path"] == "streaming"
+    monkeypatch.setenv("ADASCALE_STREAM", "2")
+    assert binding.plan(W.config(3).numel, 16)["path"] == "general"
+    monkeypatch.delenv("ADASCALE_FUSED")
+    assert binding.plan(W.config(5).numel, 64, binding.BF16)["path"] == "fused"        # no streaming kernel to prefer
+    monkeypatch.delenv("ADASCALE_STREAM")
+    # a device with a quarter of the compute units keeps a quarter of the parameters on chip
+    small = binding.plan(W.config(3).numel, 16, compute_units=64)
+    assert small["fused_grid"] == 64 and small["on_chip_percent"] == 100 * 63 // small["tiles_per_workgroup"]
+    with pytest.raises(binding.AdaScaleError):
+        binding.plan([10], 0)
+    with pytest.raises(binding.AdaScaleError):
+        binding.plan([-1], 2)
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
