@@ -370,10 +370,19 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
     monkeypatch.delenv("ADASCALE_FUSED")
     monkeypatch.delenv("ADASCALE_FUSED_MIN_PCT")
     monkeypatch.delenv("ADASCALE_STREAM")
-    for cfg, path in ((1, "fused"), (3, "fused"), (4, "fused"), (5, "streaming")):
-        g = H.make_gpu(W.config(cfg))
+    import torch
+    from paper_2007_05105_amd import binding
+    prop = torch.cuda.get_device_properties(0)
+    for cfg, path in ((1, "fused"), (2, "fused"), (3, "fused"), (4, "fused"), (5, "streaming")):
+        wl = W.config(cfg)
+        g = H.make_gpu(wl)
         assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
+        # the host-only plan for a device of this size says the same
+        plan = binding.plan(wl.numel, wl.S, wl.grad_dtype, compute_units=prop.multi_processor_count,
+                            lds_bytes=prop.shared_memory_per_block)
+        assert plan["path"] == path, (cfg, plan)
         g.close()
+    assert (prop.multi_processor_count, prop.shared_memory_per_block) == (256, 160 * 1024)   # what plan() assumes by default
     wl = W.config(5)
     g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # run-time number of half-groups
     assert g.step_path() == "streaming"
