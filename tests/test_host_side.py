@@ -1,4 +1,5 @@
-"""CPU checks of the baseline schedule tables (linear scaling with warm-up and its stretched form)."""
+"""CPU checks of host-side pieces that hold none of the method's arithmetic: the baseline schedule
+tables (linear scaling with warm-up and its stretched form) and the layout of the synthetic inputs."""
 import math
 
 import numpy as np
@@ -57,3 +58,25 @@ def test_bad_arguments():
         SCH.lsw_schedule([0.1], 0)
     with pytest.raises(ValueError):
         SCH.lsw_plus_schedule([0.1], 2, 0)
+
+
+def test_gradient_buffers_are_rows_of_one_allocation():
+    """Input layout (no arithmetic of the method): S rows of one allocation, disjoint, the same
+    tensor offsets in every row; rows of 2 MiB or more start on 2 MiB boundaries."""
+    import workloads as W
+    wl = W.custom([(5000,), (3, 7), (1,)], 4, steps=1)
+    inp = W.Inputs(wl, "cpu")
+    base = inp.g_all.data_ptr()
+    starts = [f.data_ptr() - base for f in inp.g_flat]
+    assert starts == sorted(starts) and starts[0] == 0
+    assert all(b - a >= inp.len_g * 4 and (b - a) % 256 == 0 for a, b in zip(starts, starts[1:]))
+    for row in inp.g:
+        assert [t.numel() for t in row] == list(wl.numel)
+    assert [[t.data_ptr() - f.data_ptr() for t in row] for row, f in zip(inp.g, inp.g_flat)] == \
+           [[o * 4 for o in inp.offs_g]] * 4
+    big = W.custom([(600000,)], 3, steps=1)                      # 2.4 MB per row
+    inp = W.Inputs(big, "cpu")
+    starts = [f.data_ptr() - inp.g_all.data_ptr() for f in inp.g_flat]
+    assert starts == [0, 4 << 20, 8 << 20]
+    sep = W.Inputs(wl, "cpu", one_allocation=False)
+    assert len({f.untyped_storage().data_ptr() for f in sep.g_flat}) == 4
