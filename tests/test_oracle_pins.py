@@ -368,6 +368,112 @@ def test_elastic_scale_change_keeps_state():
     assert all(b > a for a, b in zip(taus, taus[1:]))
 
 
+# ------------------------------------------------- resuming and changing the scale
+def _numpy_sample(g):
+    """A, B and the two raw estimates of App. B.3 for one [S, d] sample, from numpy."""
+    g = np.asarray(g, dtype=np.float64)
+    S = g.shape[0]
+    A, B = (g ** 2).sum(), (g.mean(axis=0) ** 2).sum()
+    sig = g.var(axis=0, ddof=1).sum() if S >= 2 else 0.0     # summed per-coordinate sample variance
+    return A, B, sig, B - sig / S
+
+
+@pytest.mark.parametrize("flags", [0, LAGGED_R, EST_M1M2])
+def test_resume_from_the_saved_state_continues_the_same_run(flags):
+    """The state of Algorithm 2 is (w, v, tau) plus the two averages of App. B.3 and their sample
+    count: a fresh oracle given exactly those continues an interrupted run bit for bit."""
+    S, d, T = 4, 40, 6
+    lr = f32(0.2 * 0.7 ** np.arange(12))
+    gs = [f32(rng(50 + t).normal(size=(S, d)) + 0.4) for t in range(T)]
+    kw = dict(theta=0.8, weight_decay=1e-3, momentum=0.9, flags=flags)
+    straight, w_a, v_a = run(S, gs, lr=lr, **kw)
+
+    o = Oracle(S, lr, **kw)
+    w, v = [np.zeros(d)], [np.zeros(d)]
+    for g in gs[:3]:
+        o.step(w, v, [[g[i]] for i in range(S)])
+    saved = o.state()
+    o2 = Oracle(S, lr, **kw)
+    o2.set_state(saved.step, saved.tau, saved.sigma2_bar, saved.mu2_bar, saved.r)
+    w2, v2 = [w[0].copy()], [v[0].copy()]
+    for t, g in enumerate(gs[3:], start=3):
+        st = o2.step(w2, v2, [[g[i]] for i in range(S)]).as_dict()
+        assert st == straight[t]
+    assert np.array_equal(w2[0], w_a) and np.array_equal(v2[0], v_a)
+
+
+def test_set_state_fields_land_where_the_next_step_reads_them():
+    """One step after set_state(k, tau, s, m), against numpy: the averages move by
+    alpha = max(1 - theta, 1/(k+1)) towards the new (clamped) sample, the learning rate is read at
+    floor(tau), the clock becomes tau + r and the count k + 1 (Sec. 3.2, App. B.3).  The four
+    values are all different, so a swapped or dropped field shows."""
+    S, d, theta, eps = 4, 25, 0.75, 1e-6
+    lr = f32(np.linspace(1.0, 0.1, 10))
+    g = f32(rng(61).normal(size=(S, d)) * 0.7 + 0.5)
+    A, B, sig, mu = _numpy_sample(g)
+    assert sig > eps and mu > 0
+    for k, tau, s0, m0 in ((2, 5.25, 3.5, 0.125), (40, 7.9, 0.25, 6.0)):
+        o = Oracle(S, lr, theta=theta, eps=eps)
+        o.set_state(k, tau, s0, m0)
+        w, v = [np.zeros(d)], [np.zeros(d)]
+        st = o.step(w, v, [[g[i]] for i in range(S)])
+        alpha = max(1 - theta, 1.0 / (k + 1))
+        s1, m1 = s0 + alpha * (sig - s0), m0 + alpha * (mu - m0)
+        r = (s1 + m1) / (s1 / S + m1)
+        np.testing.assert_allclose([st.sigma2_bar, st.mu2_bar, st.r], [s1, m1, r], rtol=1e-13)
+        np.testing.assert_allclose(st.lr_eff, r * float(lr[int(math.floor(tau))]), rtol=1e-13)
+        np.testing.assert_allclose(st.tau, tau + r, rtol=1e-14)
+        assert st.step == k + 1
+        np.testing.assert_allclose(w[0], -st.lr_eff * g.astype(np.float64).mean(axis=0), rtol=1e-12)
+
+
+@pytest.mark.parametrize("S_old,S_new", [(4, 8), (8, 3), (2, 5)])
+def test_scale_change_uses_the_new_scale_in_the_estimator(S_old, S_new):
+    """Elastic AdaScaling (Sec. 4): after the scale changes, sigma2_hat divides by S' - 1, mu2_hat
+    and the gain ratio use S' (App. B.3, eq. 3).  With theta = 0 the next gain is the plain ratio
+    of norms (A/S')/B of Sec. 3.4 -- taken here from numpy."""
+    d = 30
+    o = Oracle(S_old, f32([0.05]), theta=0.6)
+    w, v = [np.zeros(d)], [np.zeros(d)]
+    for t in range(3):
+        g = f32(rng(70 + t).normal(size=(S_old, d)) + 0.3)
+        o.step(w, v, [[g[i]] for i in range(S_old)])
+    tau_before = o.state().tau
+    o.set_scale(S_new, 0.0)
+    g = f32(rng(80).normal(size=(S_new, d)) + 0.3)
+    st = o.step(w, v, [[g[i]] for i in range(S_new)])
+    A, B, sig, mu = _numpy_sample(g)
+    assert sig > 1e-6 and mu > 0                                  # no clamp active
+    np.testing.assert_allclose([st.sum_sq, st.sq_mean, st.sigma2_hat, st.mu2_hat], [A, B, sig, mu], rtol=1e-12)
+    np.testing.assert_allclose(st.r, (A / S_new) / B, rtol=1e-12)
+    np.testing.assert_allclose([st.sigma2_bar, st.mu2_bar], [sig, mu], rtol=1e-12)   # theta = 0: no memory
+    np.testing.assert_allclose(st.tau, tau_before + st.r, rtol=1e-14)
+    assert st.step == 4                                           # the count carries on
+
+
+@pytest.mark.parametrize("S_new", [16, 100, 1500])
+def test_scale_change_default_theta_follows_the_new_scale(S_new):
+    """theta = max(1 - S'/1000, 0) after a change of scale (Sec. 3.4, Sec. 4): asking for the
+    default gives the same run as passing that value, and the averages move by
+    alpha = max(1 - theta, 1/k) = max(min(S'/1000, 1), 1/k)."""
+    d, S_old = 12, 2
+    explicit = max(1.0 - S_new / 1000.0, 0.0)
+    outs = []
+    for theta in (-1.0, explicit):
+        o = Oracle(S_old, f32([0.05]), theta=0.3)
+        w, v = [np.zeros(d)], [np.zeros(d)]
+        o.set_state(50, 11.0, 2.0, 0.5)
+        o.set_scale(S_new, theta)
+        g = f32(rng(90).normal(size=(S_new, d)) + 0.3)
+        st = o.step(w, v, [[g[i]] for i in range(S_new)])
+        outs.append((st.as_dict(), w[0].copy()))
+    assert outs[0][0] == outs[1][0] and np.array_equal(outs[0][1], outs[1][1])
+    A, B, sig, mu = _numpy_sample(g)
+    alpha = max(min(S_new / 1000.0, 1.0), 1.0 / 51)
+    np.testing.assert_allclose(outs[0][0]["sigma2_bar"], 2.0 + alpha * (max(sig, 1e-6) - 2.0), rtol=1e-12)
+    np.testing.assert_allclose(outs[0][0]["mu2_bar"], 0.5 + alpha * (max(mu, 0.0) - 0.5), rtol=1e-12)
+
+
 def test_openmp_build_agrees():
     S, d = 5, 1000
     g = f32(rng(30).normal(size=(S, d)) + 0.1)
