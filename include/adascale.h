@@ -15,7 +15,10 @@
  *   tau_{t+1} = tau_t + r_t                                Sec. 3.2
  *
  * Everything runs in the library's own HIP kernels on the caller's stream; no call except
- * adascale_get_state waits for the device.  All functions return an ADASCALE_* code and
+ * adascale_get_state waits for the device (adascale_set_scale may, see there).  What a call does
+ * depends on its arguments alone: the library reads no environment variables.  Diagnostics,
+ * benchmark instrumentation and the knobs the tests steer the choice of kernels with are declared
+ * in adascale_diag.h.  All functions return an ADASCALE_* code and
  * never throw, abort or print.  A context belongs to one device (each call makes it current while
  * it runs and leaves the caller's current device as it found it); calls on one context must
  * be issued in order on one stream at a time (the context owns scratch that consecutive
@@ -61,8 +64,11 @@ enum {
      * cheaper per step) satisfies that as soon as the compute units are free, and the library
      * chains its own fused launches on a device so that two of them never hold half the chip
      * each.  Set this flag if the process runs OTHER grid-synchronising kernels concurrently on
-     * the same device: the HIP runtime then serialises all of them.  In either mode the wait at
-     * the barrier is bounded; if it ever gives up, adascale_get_state returns ADASCALE_ESTATE. */
+     * the same device, or if OTHER PROCESSES run such kernels (this library's fused step included)
+     * on the same device: the chaining is per process, and two grids that each hold part of the
+     * chip and wait for the rest can only be told apart by the runtime.  In either mode the wait
+     * at the barrier is bounded (a few seconds); what happens when it gives up is described at
+     * adascale_get_state. */
     ADASCALE_COOPERATIVE_LAUNCH = 8u
 };
 
@@ -115,9 +121,11 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out);
  * Pointers need only element alignment (16-byte alignment is the fast case).  The host arrays
  * are copied before the call returns; the device tensors must stay valid, and the gradients
  * unmodified, until the stream work completes.  Never blocks on the device except when more
- * than a few distinct pointer sets are in flight at once, and allocates nothing except the
- * first time a context takes the general kernels (see adascale_step_path), which pass the whole
- * mean gradient through a scratch of d floats.  A tensor with numel 0 may have
+ * than a few distinct pointer sets are in flight at once (the device keeps the tables of the last
+ * eight pointer sets, so a caller that alternates between a few sets of buffers uploads nothing),
+ * and allocates nothing except the first time a context takes the general kernels (scales above
+ * 4096, see adascale_diag.h), which pass the whole mean gradient through a scratch of d floats.
+ * A tensor with numel 0 may have
  * null pointers.  EINVAL on a null required pointer, or (unless NO_POINTER_CHECK) a pointer
  * that is not device memory of sufficient extent; nothing is launched in that case.
  */
@@ -127,13 +135,20 @@ int adascale_step(adascale_ctx *ctx, void *const *w, void *const *mom, const voi
 /*
  * Copy the scalar state (Algorithm 2's tau, the gain ratio, the estimates) to host memory.
  * Waits for the work queued on hip_stream; it is the only call that synchronises.
+ * ADASCALE_ESTATE: a fused step's grid barrier gave up waiting (its workgroups were never all
+ * resident at once).  That step is void: workgroups that saw the failure left w and v of the
+ * tiles they keep on chip untouched and did not advance the state, but others may have finished,
+ * and tiles beyond the chip's capacity already hold the new momentum in v -- so w, v and the state
+ * are to be taken as lost.  From then on adascale_step on this context returns ADASCALE_ESTATE
+ * too, until the caller has restored w and v from a checkpoint and called adascale_set_state.
  */
 int adascale_get_state(adascale_ctx *ctx, adascale_state *out, void *hip_stream);
 
 /*
  * Overwrite the resumable part of the state: step count k, tau and the two moving averages
  * (the remaining fields of adascale_state are per-step diagnostics).  With (w, mom) this is
- * a full checkpoint.  Asynchronous on hip_stream.
+ * a full checkpoint.  Asynchronous on hip_stream.  Also ends the failed state described at
+ * adascale_get_state.
  */
 int adascale_set_state(adascale_ctx *ctx, int64_t step, double tau, double sigma2_bar, double mu2_bar,
                        void *hip_stream);
@@ -141,7 +156,9 @@ int adascale_set_state(adascale_ctx *ctx, int64_t step, double tau, double sigma
 /*
  * Elastic AdaScaling (Sec. 4): change the scale to S_new between steps; tau and the moving
  * averages carry on.  theta < 0 selects max(1 - S_new/1000, 0).  The next adascale_step
- * expects S_new * N gradient pointers.  EINVAL if S_new < 1 or theta >= 1.
+ * expects S_new * N gradient pointers.  EINVAL if S_new < 1 or theta >= 1.  Host only, except
+ * when S_new needs a larger pointer table than any scale before it on this context: the table is
+ * then reallocated, which waits for the device to go idle (hipDeviceSynchronize) first.
  */
 int adascale_set_scale(adascale_ctx *ctx, int32_t S_new, double theta);
 
@@ -151,75 +168,6 @@ void adascale_destroy(adascale_ctx *ctx);
 /* Message for the last non-OK code returned on this context (or by the last failed
  * adascale_init when ctx is NULL).  The string is owned by the library. */
 const char *adascale_last_error(const adascale_ctx *ctx);
-
-/* Algorithmic bytes one step moves for this context: S*d*b gradient bytes read once plus the
- * per-parameter traffic of a two-sweep step that keeps nothing on chip: 24 bytes (the new momentum
- * written and read back, v read, w read twice and written), 20 without weight decay, where the
- * first sweep does not need w.  For benchmarks; host only. */
-int64_t adascale_step_bytes(const adascale_ctx *ctx);
-
-/*
- * Which implementation the next adascale_step on this context runs; all compute the same thing
- * (the choice depends on the gradient type, the scale of the moment and the size of the
- * parameter list, and can be steered with the environment for tests and measurements):
- *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient on chip as far
- *                            as it fits (S <= 4096 and at least a fifth of the mean
- *                            gradient fitting in registers + LDS);
- *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
- *                            sweep in memory order: S <= 4096, parameter lists far larger than
- *                            the chip;
- *   ADASCALE_PATH_GENERAL    three kernels for any scale (or two with ADASCALE_LAGGED_R: one
- *                            sweep that reduces and updates, then the scalars).
- */
-enum { ADASCALE_PATH_GENERAL = 0, ADASCALE_PATH_FUSED = 1, ADASCALE_PATH_STREAMING = 2 };
-int adascale_step_path(const adascale_ctx *ctx);
-
-/* 1 if adascale_step_path is ADASCALE_PATH_FUSED, else 0. */
-int adascale_uses_fused_step(const adascale_ctx *ctx);
-
-/*
- * How the fused and streaming kernels consume the S gradients of a tile (Algorithm 1's sum over
- * the batches): in shape[1] half-groups of shape[0] loads each, alternating between two register
- * buffers; the pointer table rows are padded to shape[2] = shape[0] * shape[1] replica slots.
- * Host only, needs no device.  Returns a bit mask: 1 = the fused step has a kernel instance for
- * this gradient type and scale (at every register level, both gain variants), 2 = the streaming
- * reduce kernel has one; 0 (shape untouched) if the scale is outside their range, in which case
- * the general kernels run.  For tests and diagnostics.
- */
-int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3]);
-
-/*
- * What adascale_init would decide for cfg's parameter list, gradient type, scale and flags on a
- * device with `compute_units` compute units and `lds_bytes` of LDS per workgroup (MI355X: 256 and
- * 163840): how the list splits into whole 512-lane tiles (2048 elements, inside one tensor) and
- * ragged last tiles, the grids, how many tiles of the mean gradient each workgroup of the fused
- * step keeps in registers and in LDS, and the path.  Host only: no device is touched, cfg's
- * lr_table, device and the optimizer constants are not read.  The fields of a path that does not
- * apply are 0.  (adascale_init additionally asks the runtime whether the fused grid can be
- * resident at once; on MI355X it can.)  For tests and diagnostics.
- */
-typedef struct {
-    int64_t full_tiles, ragged_tiles;
-    int32_t path;                 /* ADASCALE_PATH_* */
-    int32_t fused_grid;           /* workgroups of the fused step, one per compute unit at most */
-    int32_t tiles_per_workgroup;  /* whole tiles per workgroup, rounded up */
-    int32_t register_tiles;       /* of those, kept in registers ... */
-    int32_t lds_tiles;            /* ... and in LDS; the rest passes through memory */
-    int32_t on_chip_percent;
-    int32_t stream_grid;          /* workgroups of the streaming reduce kernel */
-} adascale_plan_info;
-int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds_bytes, adascale_plan_info *out);
-
-/*
- * Benchmark instrumentation: while profiling is on, every adascale_step also records HIP
- * events on its stream before and after each of its kernels (up to max_steps steps).
- * adascale_profile_end waits for the stream work, writes the average duration in
- * milliseconds of the reduce, scalars and update kernels over the recorded steps to ms[0..2]
- * (a fused step reports its single kernel in ms[0])
- * and the number of recorded steps to *n_steps, and turns profiling off.
- */
-int adascale_profile_begin(adascale_ctx *ctx, int32_t max_steps);
-int adascale_profile_end(adascale_ctx *ctx, double ms[3], int32_t *n_steps);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,5 @@
-"""ctypes binding of include/adascale.h: same entry points, argument marshalling only.
+"""ctypes binding of include/adascale.h and include/adascale_diag.h: same entry points, argument
+marshalling only.
 
 PyTorch appears here only as the owner of device memory and streams: tensors are passed
 down as raw device pointers and the current stream as a raw hipStream_t.  There is no
@@ -16,10 +17,15 @@ F32, BF16 = 0, 1
 LAGGED_R, EST_NORM_RATIO, NO_POINTER_CHECK, COOPERATIVE_LAUNCH = 1, 2, 4, 8
 _CODES = {0: "OK", 1: "EINVAL", 2: "ENOMEM", 3: "EHIP", 4: "ESTATE"}
 
+FORCE_NONE, FORCE_GENERAL, FORCE_FUSED, FORCE_STREAMING = 0, 1, 2, 3
+
+# adascale.h: the interface of the method
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
-           "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_bytes",
-           "adascale_profile_begin", "adascale_profile_end", "adascale_uses_fused_step",
-           "adascale_step_path", "adascale_kernel_shape", "adascale_plan"]
+           "adascale_set_scale", "adascale_destroy", "adascale_last_error"]
+# adascale_diag.h: diagnostics, instrumentation, test knobs
+EXPORTS_DIAG = ["adascale_step_bytes", "adascale_step_moved_bytes", "adascale_profile_begin", "adascale_profile_end",
+                "adascale_uses_fused_step", "adascale_step_path", "adascale_kernel_shape", "adascale_plan",
+                "adascale_init_tuned", "adascale_fail_next_barrier"]
 
 
 class AdaScaleError(RuntimeError):
@@ -43,6 +49,12 @@ class State(C.Structure):
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Tuning(C.Structure):
+    """adascale_tuning: knobs for tests and measurements; all zero = the library's own choices."""
+    _fields_ = [("force_path", C.c_int32), ("fused_max_grid", C.c_int32), ("fused_min_percent", C.c_int32),
+                ("stream_via_scratch", C.c_int32), ("barrier_spin_limit", C.c_int64)]
 
 
 class PlanInfo(C.Structure):
@@ -96,8 +108,14 @@ def load_library() -> C.CDLL:
         lib.adascale_step_path.restype = C.c_int
         lib.adascale_kernel_shape.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         lib.adascale_kernel_shape.restype = C.c_int
-        lib.adascale_plan.argtypes = [C.POINTER(Config), C.c_int32, C.c_int64, C.POINTER(PlanInfo)]
+        lib.adascale_plan.argtypes = [C.POINTER(Config), C.POINTER(Tuning), C.c_int32, C.c_int64, C.POINTER(PlanInfo)]
         lib.adascale_plan.restype = C.c_int
+        lib.adascale_init_tuned.argtypes = [C.POINTER(Config), C.POINTER(Tuning), C.POINTER(C.c_void_p)]
+        lib.adascale_init_tuned.restype = C.c_int
+        lib.adascale_fail_next_barrier.argtypes = [C.c_void_p]
+        lib.adascale_fail_next_barrier.restype = C.c_int
+        lib.adascale_step_moved_bytes.argtypes = [C.c_void_p]
+        lib.adascale_step_moved_bytes.restype = C.c_int64
         _lib = lib
     return _lib
 
@@ -110,14 +128,15 @@ def kernel_shape(grad_dtype: int, S: int):
 
 
 def plan(numel: Sequence[int], S: int, grad_dtype: int = F32, flags: int = 0, compute_units: int = 256,
-         lds_bytes: int = 160 * 1024) -> dict:
+         lds_bytes: int = 160 * 1024, tuning: Optional[Tuning] = None) -> dict:
     """adascale_plan: what adascale_init would decide for this parameter list on a device with the
     given compute units and LDS per workgroup (defaults: MI355X); needs no device."""
     lib = load_library()
     n = (C.c_int64 * len(numel))(*[int(x) for x in numel])
     cfg = Config(S, len(numel), n, grad_dtype, 0.0, 0.0, -1.0, 0.0, None, 0, 0, flags)
     info = PlanInfo()
-    rc = lib.adascale_plan(C.byref(cfg), compute_units, lds_bytes, C.byref(info))
+    rc = lib.adascale_plan(C.byref(cfg), C.byref(tuning) if tuning is not None else None, compute_units, lds_bytes,
+                           C.byref(info))
     if rc != 0:
         raise AdaScaleError(rc, lib.adascale_last_error(None).decode())
     d = info.as_dict()
@@ -134,14 +153,17 @@ class AdaScale:
 
     def __init__(self, numel: Sequence[int], S: int, lr_table, momentum: float = 0.9,
                  weight_decay: float = 0.0, theta: float = -1.0, eps: float = 1e-6,
-                 grad_dtype: int = F32, device: int = 0, flags: int = 0):
+                 grad_dtype: int = F32, device: int = 0, flags: int = 0, tuning: Optional[Tuning] = None):
         self._lib = load_library()
         self._h = C.c_void_p()
         n = (C.c_int64 * len(numel))(*[int(x) for x in numel])
         lr = np.ascontiguousarray(lr_table, dtype=np.float32)
         cfg = Config(S, len(numel), n, grad_dtype, momentum, weight_decay, theta, eps,
                      lr.ctypes.data_as(C.POINTER(C.c_float)), lr.size, device, flags)
-        rc = self._lib.adascale_init(C.byref(cfg), C.byref(self._h))
+        if tuning is None:
+            rc = self._lib.adascale_init(C.byref(cfg), C.byref(self._h))
+        else:
+            rc = self._lib.adascale_init_tuned(C.byref(cfg), C.byref(tuning), C.byref(self._h))
         if rc != 0:
             raise AdaScaleError(rc, self._lib.adascale_last_error(None).decode())
         self.S, self.numel, self.grad_dtype, self.device = S, list(numel), grad_dtype, device
@@ -220,6 +242,12 @@ class AdaScale:
 
     def step_bytes(self) -> int:
         return int(self._lib.adascale_step_bytes(self._h))
+
+    def step_moved_bytes(self) -> int:
+        return int(self._lib.adascale_step_moved_bytes(self._h))
+
+    def fail_next_barrier(self) -> None:
+        self._check(self._lib.adascale_fail_next_barrier(self._h))
 
     def last_error(self) -> str:
         return self._lib.adascale_last_error(self._h).decode()

@@ -61,13 +61,24 @@ struct adascale_ctx {
     std::vector<unsigned long long> cold_base;  // per tensor: address that tensor's element 0 would have
     long long d = 0;
     int vec = 4, tile = 1024;
-    int n_tiles = 0, span_tiles = 2, n_spans = 0, max_blocks = 1 << 30, group = 0;
-    int update_reverse = 0;
+    int n_tiles = 0, span_tiles = 2, n_spans = 0;
     int S_cap = 0;                  // pointer table capacity in replica slots per row
+    adascale_tuning tun{};          // knobs of adascale_init_tuned (all zero: the library's choices)
+    bool failed = false;            // a fused step's grid barrier gave up (seen by adascale_get_state)
+    bool fail_next = false;         // adascale_fail_next_barrier
 
     int *d_span_first = nullptr, *d_tile_prefix = nullptr;
     long long *d_numel = nullptr;
-    unsigned long long *d_ptrs = nullptr;
+    // The device keeps the pointer tables of the last kTables distinct pointer sets; table j's
+    // pinned host mirror h_tab[j] is also the staging buffer it is uploaded from.
+    unsigned long long *d_tab[kTables] = {};
+    unsigned long long *h_tab[kTables] = {};
+    hipEvent_t tab_ev[kTables] = {};   // upload of table j
+    bool tab_uploaded[kTables] = {};   // tab_ev[j] has been recorded
+    size_t tab_len[kTables] = {};      // 0: table j holds nothing
+    unsigned long long tab_used[kTables] = {};  // step count of the last use (the oldest is replaced)
+    unsigned long long steps_issued = 0;
+    std::vector<unsigned long long> tab_build;  // the table of the current call
     float *d_gbar = nullptr, *d_lr = nullptr;
     double *d_partials = nullptr;
     DevState *d_state = nullptr;     // two records: [cur] is current, a step writes [cur ^ 1]
@@ -90,12 +101,6 @@ struct adascale_ctx {
     unsigned long long stream_launches = 0;
 
     DevState *h_state = nullptr;    // pinned
-    unsigned long long *h_ring[kRing] = {};
-    hipEvent_t ring_ev[kRing] = {};
-    bool ring_used[kRing] = {};
-    int ring_next = 0;
-    std::vector<unsigned long long> last_table;  // what the device table holds
-    bool table_valid = false;
 
     std::vector<hipEvent_t> prof_ev;  // 4 per recorded step
     int prof_cap = 0, prof_n = 0;
@@ -140,14 +145,6 @@ struct DeviceGuard {
     }
 };
 
-int env_int(const char *name, int dflt)
-{
-    const char *s = getenv(name);
-    if (!s || !*s) return dflt;
-    const long v = strtol(s, nullptr, 10);
-    return v > 0 ? (int)v : dflt;
-}
-
 // Replica slots in a pointer-table row: the 512-lane kernels read whole half-groups, so rows are
 // padded to their HG * NH slots (the padding repeats the last replica).
 int padded_scale(int dtype, int S);
@@ -156,25 +153,30 @@ size_t table_len(const adascale_ctx *c, int S)
     return (size_t)c->numel.size() * (size_t)(padded_scale(c->cfg.grad_dtype, S) + kRowG);
 }
 
+void forget_tables(adascale_ctx *c)
+{
+    for (int j = 0; j < kTables; ++j) c->tab_len[j] = 0;
+}
+
 int alloc_pointer_tables(adascale_ctx *c, int S)
 {
     const int slots = padded_scale(c->cfg.grad_dtype, S);
     if (slots <= c->S_cap) return ADASCALE_OK;
     const size_t bytes = std::max<size_t>(table_len(c, S), 1) * sizeof(unsigned long long);
-    if (c->d_ptrs) {
-        HIP_TRY(c, hipDeviceSynchronize());
-        HIP_TRY(c, hipFree(c->d_ptrs));
-        c->d_ptrs = nullptr;
+    if (c->d_tab[0]) HIP_TRY(c, hipDeviceSynchronize());  // kernels in flight may still read the old tables
+    for (int j = 0; j < kTables; ++j) {
+        if (c->d_tab[j]) HIP_TRY(c, hipFree(c->d_tab[j]));
+        c->d_tab[j] = nullptr;
+        if (c->h_tab[j]) HIP_TRY(c, hipHostFree(c->h_tab[j]));
+        c->h_tab[j] = nullptr;
+        c->tab_uploaded[j] = false;
     }
-    for (int i = 0; i < kRing; ++i) {
-        if (c->h_ring[i]) HIP_TRY(c, hipHostFree(c->h_ring[i]));
-        c->h_ring[i] = nullptr;
-        c->ring_used[i] = false;
+    for (int j = 0; j < kTables; ++j) {
+        HIP_TRY(c, hipMalloc(&c->d_tab[j], bytes));
+        HIP_TRY(c, hipHostMalloc(&c->h_tab[j], bytes, hipHostMallocDefault));
     }
-    HIP_TRY(c, hipMalloc(&c->d_ptrs, bytes));
-    for (int i = 0; i < kRing; ++i) HIP_TRY(c, hipHostMalloc(&c->h_ring[i], bytes, hipHostMallocDefault));
     c->S_cap = slots;
-    c->table_valid = false;
+    forget_tables(c);
     return ADASCALE_OK;
 }
 
@@ -272,9 +274,9 @@ bool plan_tiles(const long long *numel, int N, long long *full, long long *ragge
 }
 
 // May the streaming reduce kernel run on this device at all (its grid: plan_stream_grid)?
-bool plan_stream_ok(size_t lds_per_workgroup)
+bool plan_stream_ok(const adascale_tuning &tun, size_t lds_per_workgroup)
 {
-    if (env_int("ADASCALE_STREAM", 1) == 2) return false;  // 2 = keep to the plain reduce kernel
+    if (tun.force_path == ADASCALE_FORCE_GENERAL) return false;
     return lds_per_workgroup >= kStreamLdsPad + 1024;
 }
 
@@ -292,12 +294,13 @@ struct FusedPlan {
     int grid = 0, tpb = 0, level = 0, lds_cap = 0, on_chip_pct = 0;
 };
 
-FusedPlan plan_fused(long long nt, long long nc, int cus_of_device, size_t lds_per_workgroup, bool stream_ok)
+FusedPlan plan_fused(const adascale_tuning &tun, long long nt, long long nc, int cus_of_device, size_t lds_per_workgroup,
+                     bool stream_ok)
 {
     FusedPlan f;
-    if (env_int("ADASCALE_FUSED", 1) == 2) return f;  // 2 = force the three-kernel step
+    if (tun.force_path == ADASCALE_FORCE_GENERAL || tun.force_path == ADASCALE_FORCE_STREAMING) return f;
     if (nt + nc == 0) return f;
-    const int cus = std::min(std::min(cus_of_device, kFMaxGrid), env_int("ADASCALE_FUSED_GRID", kFMaxGrid));
+    const int cus = std::min(std::min(cus_of_device, kFMaxGrid), tun.fused_max_grid > 0 ? tun.fused_max_grid : kFMaxGrid);
     f.grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
     f.tpb = (int)((nt + f.grid - 1) / f.grid);
     // register-slot level: the highest whose slot count every workgroup can fill
@@ -307,7 +310,8 @@ FusedPlan plan_fused(long long nt, long long nc, int cus_of_device, size_t lds_p
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
     // kernel is the faster one (measured crossover: 13-25 % on chip, depending on S and gradient type)
     f.on_chip_pct = f.tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(f.level) + std::min(f.tpb, f.lds_cap)) / f.tpb);
-    if (stream_ok && f.on_chip_pct < env_int("ADASCALE_FUSED_MIN_PCT", kFusedMinPct)) return f;
+    const int min_pct = tun.force_path == ADASCALE_FORCE_FUSED ? 0 : tun.fused_min_percent > 0 ? tun.fused_min_percent : kFusedMinPct;
+    if (stream_ok && f.on_chip_pct < min_pct) return f;
     f.ok = true;
     return f;
 }
@@ -347,7 +351,7 @@ int setup_tiles(adascale_ctx *c)
     }
     c->tiles_ok = true;
 
-    if (!plan_stream_ok(prop.sharedMemPerBlock)) return ADASCALE_OK;
+    if (!plan_stream_ok(c->tun, prop.sharedMemPerBlock)) return ADASCALE_OK;
     c->s_grid = plan_stream_grid((long long)nt, (long long)nc, c->n_cus);
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
@@ -356,7 +360,7 @@ int setup_tiles(adascale_ctx *c)
     }
     HIP_TRY(c, hipMalloc(&c->d_claim, 2 * sizeof(unsigned)));
     HIP_TRY(c, hipMemset(c->d_claim, 0, 2 * sizeof(unsigned)));
-    c->stream_momentum = env_int("ADASCALE_STREAM_MOMENTUM", 1) == 1;  // 2: mean gradient through the scratch
+    c->stream_momentum = c->tun.stream_via_scratch != 1;
     c->stream_ok = true;
     return ADASCALE_OK;
 }
@@ -371,8 +375,8 @@ int setup_fused(adascale_ctx *c)
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
     if ((c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) && !prop.cooperativeLaunch) return ADASCALE_OK;
-    const FusedPlan f = plan_fused((long long)c->ftiles.size(), (long long)c->ctiles.size(), prop.multiProcessorCount,
-                                   prop.sharedMemPerBlock, c->stream_ok);
+    const FusedPlan f = plan_fused(c->tun, (long long)c->ftiles.size(), (long long)c->ctiles.size(),
+                                   prop.multiProcessorCount, prop.sharedMemPerBlock, c->stream_ok);
     if (!f.ok) return ADASCALE_OK;
     const size_t lds_bytes = (size_t)f.lds_cap * kFThreads * sizeof(f4);
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
@@ -393,81 +397,40 @@ int setup_fused(adascale_ctx *c)
 }
 
 template <typename GT>
-void launch_reduce(const adascale_ctx *c, int grid, hipStream_t s, int S)
+void launch_reduce(const adascale_ctx *c, const unsigned long long *d_ptrs, int grid, hipStream_t s, int S)
 {
     const double inv_S = 1.0 / (double)S;
     const int row_len = padded_scale(c->cfg.grad_dtype, S) + kRowG;
 #define LAUNCH(HH)                                                                                   \
     hipLaunchKernelGGL((k_reduce<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,        \
-                       c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, c->n_tiles,           \
+                       c->d_tile_prefix, c->d_numel, d_ptrs, c->d_partials, c->n_tiles,              \
                        c->span_tiles, c->n_spans, S, row_len, inv_S)
-    const int H = c->group > 0 ? c->group : 8;  // replicas per half-group (two half-groups in flight)
-    if (S >= 16 && H >= 8) LAUNCH(8);
-    else if (S >= 8 && H >= 4) LAUNCH(4);
-    else if (S >= 4 && H >= 2) LAUNCH(2);
+    // replicas per half-group (two half-groups in flight)
+    if (S >= 16) LAUNCH(8);
+    else if (S >= 8) LAUNCH(4);
+    else if (S >= 4) LAUNCH(2);
     else LAUNCH(1);
 #undef LAUNCH
 }
 
 template <typename GT>
-void launch_reduce_update(const adascale_ctx *c, int grid, hipStream_t s, int S, const DevState *st, const ScalarArgs &sa)
+void launch_reduce_update(const adascale_ctx *c, const unsigned long long *d_ptrs, int grid, hipStream_t s, int S,
+                          const DevState *st, const ScalarArgs &sa)
 {
     const double inv_S = 1.0 / (double)S;
     const int row_len = padded_scale(c->cfg.grad_dtype, S) + kRowG;
     const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
 #define LAUNCH(HH)                                                                                         \
     hipLaunchKernelGGL((k_reduce_update<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,       \
-                       c->d_tile_prefix, c->d_numel, c->d_ptrs, c->d_partials, st, c->d_lr, sa, c->n_tiles, \
+                       c->d_tile_prefix, c->d_numel, d_ptrs, c->d_partials, st, c->d_lr, sa, c->n_tiles,    \
                        c->span_tiles, c->n_spans, S, row_len, inv_S, rho, lambda)
-    const int H = c->group > 0 ? c->group : 8;
-    if (S >= 16 && H >= 8) LAUNCH(8);
-    else if (S >= 8 && H >= 4) LAUNCH(4);
-    else if (S >= 4 && H >= 2) LAUNCH(2);
+    if (S >= 16) LAUNCH(8);
+    else if (S >= 8) LAUNCH(4);
+    else if (S >= 4) LAUNCH(2);
     else LAUNCH(1);
 #undef LAUNCH
 }
 
-#ifdef ADASCALE_FUSED_TIMING
-// Development builds only: every workgroup of the fused kernel leaves wall-clock stamps of its
-// phases; after 60 launches the host prints their spread, overall and per XCD, once.
-hipError_t fused_timing_hook(adascale_ctx *c, FusedArgs *fa)
-{
-    static unsigned long long *d_timing = nullptr;
-    if (!d_timing) {
-        const hipError_t e = hipMalloc(&d_timing, sizeof(unsigned long long) * 8 * kFMaxGrid);
-        if (e != hipSuccess) return e;
-    }
-    fa->timing = d_timing;
-    if (c->fused_launches != 60) return hipSuccess;
-    std::vector<unsigned long long> h(8 * kFMaxGrid);
-    const hipError_t e = hipMemcpy(h.data(), d_timing, h.size() * 8, hipMemcpyDeviceToHost);
-    if (e != hipSuccess) return e;
-    unsigned long long t0 = ~0ULL;
-    for (int i = 0; i < c->f_grid; ++i) t0 = std::min(t0, h[8 * i]);
-    for (int j = 0; j < 8; ++j) {
-        unsigned long long mn = ~0ULL, mx = 0;
-        double sum = 0;
-        for (int i = 0; i < c->f_grid; ++i) {
-            const unsigned long long v = h[8 * i + j] - t0;
-            mn = std::min(mn, v);
-            mx = std::max(mx, v);
-            sum += v;
-        }
-        fprintf(stderr, "stamp %d: min %.2f us  mean %.2f us  max %.2f us\n", j, mn / 100.0, sum / c->f_grid / 100.0, mx / 100.0);
-    }
-    for (int x = 0; x < 8; ++x) {
-        double s2 = 0, s4 = 0;
-        int n = 0;
-        for (int i = x; i < c->f_grid; i += 8) {
-            s2 += h[8 * i + 2] - t0;
-            s4 += (h[8 * i + 4] - h[8 * i + 3]);
-            ++n;
-        }
-        if (n) fprintf(stderr, "xcd %d: phase1 end mean %.2f us, phase2 mean %.2f us\n", x, s2 / n / 100.0, s4 / n / 100.0);
-    }
-    return hipSuccess;
-}
-#endif
 
 }  // namespace
 
@@ -506,8 +469,10 @@ int adascale_kernel_shape(int32_t grad_dtype, int32_t S, int32_t shape[3])
     return (fused ? 1 : 0) | (stream_kernel_for(grad_dtype, S) ? 2 : 0);
 }
 
-int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds_bytes, adascale_plan_info *out)
+int adascale_plan(const adascale_config *cfg, const adascale_tuning *tuning, int32_t compute_units, int64_t lds_bytes,
+                  adascale_plan_info *out)
 {
+    const adascale_tuning tun = tuning ? *tuning : adascale_tuning{};
     if (!cfg || !out || cfg->S < 1 || cfg->n_tensors < 0 || (cfg->n_tensors > 0 && !cfg->numel) || compute_units < 1 ||
         lds_bytes < 0 || (cfg->grad_dtype != ADASCALE_F32 && cfg->grad_dtype != ADASCALE_BF16))
         return fail(nullptr, ADASCALE_EINVAL, "bad argument to adascale_plan");
@@ -523,9 +488,9 @@ int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds
     if (!tiles_ok) return ADASCALE_OK;
     out->full_tiles = full;
     out->ragged_tiles = ragged;
-    const bool stream_ok = plan_stream_ok((size_t)lds_bytes);
+    const bool stream_ok = plan_stream_ok(tun, (size_t)lds_bytes);
     if (stream_ok) out->stream_grid = plan_stream_grid(full, ragged, compute_units);
-    const FusedPlan f = plan_fused(full, ragged, compute_units, (size_t)lds_bytes, stream_ok);
+    const FusedPlan f = plan_fused(tun, full, ragged, compute_units, (size_t)lds_bytes, stream_ok);
     const bool lag = (cfg->flags & ADASCALE_LAGGED_R) != 0;
     if (f.ok) {
         out->fused_grid = f.grid;
@@ -541,7 +506,48 @@ int adascale_plan(const adascale_config *cfg, int32_t compute_units, int64_t lds
 
 int adascale_uses_fused_step(const adascale_ctx *c) { return adascale_step_path(c) == ADASCALE_PATH_FUSED ? 1 : 0; }
 
-int adascale_init(const adascale_config *cfg, adascale_ctx **out)
+int adascale_fail_next_barrier(adascale_ctx *c)
+{
+    if (!c) return ADASCALE_EINVAL;
+    if (adascale_step_path(c) != ADASCALE_PATH_FUSED || (c->cfg.flags & ADASCALE_LAGGED_R))
+        return fail(c, ADASCALE_ESTATE, "the next step has no grid barrier");
+    c->fail_next = true;
+    return ADASCALE_OK;
+}
+
+int64_t adascale_step_moved_bytes(const adascale_ctx *c)
+{
+    if (!c) return 0;
+    const int64_t b = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
+    const bool decay = c->cfg.weight_decay != 0.0, lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
+    const int64_t grads = (int64_t)c->cfg.S * c->d * b;
+    const int path = adascale_step_path(c);
+    if (path == ADASCALE_PATH_GENERAL) return grads + (lag ? 16 : 24) * c->d;  // one sweep / mean gradient out and in
+    int64_t ragged = 0;  // elements in ragged last tiles
+    for (const FTile &t : c->ctiles) ragged += c->numel[t.k] - (int64_t)t.local * kFTile;
+    const int64_t full = (int64_t)c->ftiles.size() * kFTile;
+    const int64_t in_sweep = decay ? 24 : 20;  // v read and written (w read) in the sweep; w, v read and w written after it
+    if (path == ADASCALE_PATH_STREAMING) {
+        if (!c->stream_momentum) return grads + 24 * c->d;
+        // ragged tiles: mean gradient out and in, then w, v read and v written, then the update pass
+        return grads + in_sweep * full + 32 * ragged;
+    }
+    // fused: workgroup b holds full tiles b, b + G, ...; the first q_hbm of them stay on chip
+    int regs = 0;
+    (void)fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag, &regs);
+    const int q_hbm = std::min(regs + std::max(0, std::min(c->f_tpb - regs, c->f_lds_cap)), c->f_tpb);
+    const int64_t nt = (int64_t)c->ftiles.size();
+    int64_t on_chip = 0;
+    for (int g = 0; g < c->f_grid; ++g) {
+        const int64_t n_valid = g < nt ? (nt - 1 - g) / c->f_grid + 1 : 0;
+        on_chip += std::min<int64_t>(n_valid, q_hbm);
+    }
+    return grads + 16 * on_chip * kFTile + in_sweep * (nt - on_chip) * kFTile + 24 * ragged;
+}
+
+int adascale_init(const adascale_config *cfg, adascale_ctx **out) { return adascale_init_tuned(cfg, nullptr, out); }
+
+int adascale_init_tuned(const adascale_config *cfg, const adascale_tuning *tuning, adascale_ctx **out)
 {
     if (out) *out = nullptr;
     if (!cfg || !out) return fail(nullptr, ADASCALE_EINVAL, "null cfg or out");
@@ -559,6 +565,10 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         return fail(nullptr, ADASCALE_EINVAL, "unknown flag bits");
     for (int k = 0; k < cfg->n_tensors; ++k)
         if (cfg->numel[k] < 0) return fail(nullptr, ADASCALE_EINVAL, "negative numel");
+    if (tuning && (tuning->force_path < ADASCALE_FORCE_NONE || tuning->force_path > ADASCALE_FORCE_STREAMING ||
+                   tuning->fused_max_grid < 0 || tuning->fused_min_percent < 0 || tuning->fused_min_percent > 100 ||
+                   tuning->barrier_spin_limit < 0 || (tuning->stream_via_scratch != 0 && tuning->stream_via_scratch != 1)))
+        return fail(nullptr, ADASCALE_EINVAL, "bad tuning record");
 
     adascale_ctx *c = new (std::nothrow) adascale_ctx();
     if (!c) return fail(nullptr, ADASCALE_ENOMEM, "host allocation failed");
@@ -569,10 +579,7 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
     if (c->cfg.eps <= 0.0) c->cfg.eps = 1e-6;
     c->vec = cfg->grad_dtype == ADASCALE_F32 ? 4 : 8;
     c->tile = kThreads * c->vec;
-    c->span_tiles = env_int("ADASCALE_SPAN_TILES", 2);
-    c->max_blocks = env_int("ADASCALE_MAX_BLOCKS", 1 << 30);
-    c->group = env_int("ADASCALE_GROUP", 0);
-    c->update_reverse = env_int("ADASCALE_UPDATE_REVERSE", 0);
+    if (tuning) c->tun = *tuning;
 
     const int N = cfg->n_tensors;
     c->numel.assign(cfg->numel, cfg->numel + N);
@@ -622,7 +629,7 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out)
         HIP_TRY(c, hipMemset(c->d_fault, 0, sizeof(int)));
         HIP_TRY(c, hipMemset(c->d_barrier, 0, sizeof(unsigned long long)));
         HIP_TRY(c, hipHostMalloc(&c->h_state, sizeof(DevState) + sizeof(int), hipHostMallocDefault));
-        for (int i = 0; i < kRing; ++i) HIP_TRY(c, hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
+        for (int j = 0; j < kTables; ++j) HIP_TRY(c, hipEventCreateWithFlags(&c->tab_ev[j], hipEventDisableTiming));
         HIP_TRY(c, hipMemcpy(c->d_span_first, c->span_first.data(), sizeof(int) * c->span_first.size(),
                              hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_tile_prefix, c->tile_prefix.data(), sizeof(int) * (N + 1), hipMemcpyHostToDevice));
@@ -656,7 +663,6 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_span_first);
     (void)hipFree(c->d_tile_prefix);
     (void)hipFree(c->d_numel);
-    (void)hipFree(c->d_ptrs);
     (void)hipFree(c->d_gbar);
     (void)hipFree(c->d_cold_gbar);
     (void)hipFree(c->d_lr);
@@ -668,9 +674,10 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_ctiles);
     (void)hipFree(c->d_claim);
     if (c->h_state) (void)hipHostFree(c->h_state);
-    for (int i = 0; i < kRing; ++i) {
-        if (c->h_ring[i]) (void)hipHostFree(c->h_ring[i]);
-        if (c->ring_ev[i]) (void)hipEventDestroy(c->ring_ev[i]);
+    for (int j = 0; j < kTables; ++j) {
+        (void)hipFree(c->d_tab[j]);
+        if (c->h_tab[j]) (void)hipHostFree(c->h_tab[j]);
+        if (c->tab_ev[j]) (void)hipEventDestroy(c->tab_ev[j]);
     }
     for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
     delete c;
@@ -687,7 +694,7 @@ int adascale_set_scale(adascale_ctx *c, int32_t S_new, double theta)
     if (rc != ADASCALE_OK) return rc;
     c->cfg.S = S_new;
     c->cfg.theta = theta < 0.0 ? std::max(1.0 - S_new / 1000.0, 0.0) : theta;
-    c->table_valid = false;
+    forget_tables(c);  // their rows have the old scale's length
     return ADASCALE_OK;
 }
 
@@ -699,8 +706,9 @@ int adascale_set_state(adascale_ctx *c, int64_t step, double tau, double sigma2_
     DeviceGuard guard;
     HIP_TRY(c, guard.enter(c->cfg.device));
     hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_state + c->cur, (long long)step,
-                       tau, sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len);
+                       tau, sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len, c->d_fault);
     HIP_TRY(c, hipGetLastError());
+    c->failed = false;
     return ADASCALE_OK;
 }
 
@@ -715,7 +723,11 @@ int adascale_get_state(adascale_ctx *c, adascale_state *out, void *hip_stream)
     HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state + c->cur, sizeof(DevState), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipMemcpyAsync(h_fault, c->d_fault, sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
-    if (*h_fault) return fail(c, ADASCALE_ESTATE, "a fused step gave up waiting at its grid barrier; results are invalid");
+    if (*h_fault) {
+        c->failed = true;
+        return fail(c, ADASCALE_ESTATE, "a fused step gave up waiting at its grid barrier: w, v and the state are invalid; "
+                                        "restore them and call adascale_set_state");
+    }
     const DevState &h = *c->h_state;
     out->step = h.step;
     out->tau = h.tau;
@@ -741,21 +753,27 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     DeviceGuard guard;
     HIP_TRY(c, guard.enter(c->cfg.device));
 
+    if (c->failed)
+        return fail(c, ADASCALE_ESTATE, "an earlier step failed at its grid barrier; restore w, v and call adascale_set_state");
+
     // the general kernels pass the whole mean gradient through memory
     const int path = adascale_step_path(c);
     if (!c->d_gbar && (path == ADASCALE_PATH_GENERAL || (path == ADASCALE_PATH_STREAMING && !c->stream_momentum))) {
         HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * c->gbar_len));
-        c->table_valid = false;
+        forget_tables(c);  // they point at the ragged-tile scratch
     }
 
-    // Build the device pointer table [N][3 + S] in a pinned slot; upload only when it changed.
+    // The device pointer table [N][3 + S'] of this call.  The device keeps the tables of the last
+    // kTables distinct pointer sets, so a caller that alternates between a few sets of buffers
+    // uploads nothing; a new set replaces the one used longest ago.
     const int S_pad = padded_scale(c->cfg.grad_dtype, S);
     const int row_len = S_pad + kRowG;
     const size_t len = table_len(c, S);
+    const unsigned long long *d_ptrs = c->d_tab[0];
+    c->steps_issued += 1;
     if (len > 0) {
-        int slot = c->ring_next;
-        if (c->ring_used[slot]) HIP_TRY(c, hipEventSynchronize(c->ring_ev[slot]));
-        unsigned long long *tab = c->h_ring[slot];
+        c->tab_build.resize(len);
+        unsigned long long *tab = c->tab_build.data();
         for (int k = 0; k < N; ++k) {
             unsigned long long *row = tab + (size_t)k * row_len;
             row[kRowW] = (unsigned long long)(uintptr_t)w[k];
@@ -764,9 +782,10 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             for (int i = 0; i < S_pad; ++i)
                 row[kRowG + i] = (unsigned long long)(uintptr_t)grads[(size_t)std::min(i, S - 1) * N + k];
         }
-        const bool same = c->table_valid && c->last_table.size() == len &&
-                          memcmp(c->last_table.data(), tab, len * sizeof(unsigned long long)) == 0;
-        if (!same) {
+        int slot = -1;
+        for (int j = 0; j < kTables && slot < 0; ++j)
+            if (c->tab_len[j] == len && memcmp(c->h_tab[j], tab, len * sizeof(unsigned long long)) == 0) slot = j;
+        if (slot < 0) {
             const size_t gb = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
             uintptr_t lo = 1, hi = 0;
             for (int k = 0; k < N; ++k) {
@@ -783,13 +802,21 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
                                     c->numel[k]);
                 }
             }
-            HIP_TRY(c, hipMemcpyAsync(c->d_ptrs, tab, len * sizeof(unsigned long long), hipMemcpyHostToDevice, s));
-            HIP_TRY(c, hipEventRecord(c->ring_ev[slot], s));
-            c->ring_used[slot] = true;
-            c->ring_next = (slot + 1) % kRing;
-            c->last_table.assign(tab, tab + len);
-            c->table_valid = true;
+            slot = 0;  // an empty table if there is one, else the one used longest ago
+            for (int j = 1; j < kTables && c->tab_len[slot] != 0; ++j)
+                if (c->tab_len[j] == 0 || c->tab_used[j] < c->tab_used[slot]) slot = j;
+            // the mirror is the staging buffer: its last upload must have left it (long ago, normally)
+            if (c->tab_uploaded[slot]) HIP_TRY(c, hipEventSynchronize(c->tab_ev[slot]));
+            c->tab_len[slot] = 0;
+            memcpy(c->h_tab[slot], tab, len * sizeof(unsigned long long));
+            // stream order puts the copy behind every earlier kernel that reads this table
+            HIP_TRY(c, hipMemcpyAsync(c->d_tab[slot], c->h_tab[slot], len * sizeof(unsigned long long), hipMemcpyHostToDevice, s));
+            HIP_TRY(c, hipEventRecord(c->tab_ev[slot], s));
+            c->tab_uploaded[slot] = true;
+            c->tab_len[slot] = len;
         }
+        c->tab_used[slot] = c->steps_issued;
+        d_ptrs = c->d_tab[slot];
     }
 
     hipEvent_t *pe = nullptr;
@@ -808,13 +835,16 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.cold = c->d_ctiles;
         fa.n_cold = (int)c->ctiles.size();
         fa.numel = c->d_numel;
-        fa.ptrs = c->d_ptrs;
+        fa.ptrs = d_ptrs;
         fa.partials = c->d_partials;
         fa.st_in = st_in;
         fa.st_out = st_out;
         fa.lr = c->d_lr;
         fa.barrier = c->d_barrier;
         fa.barrier_target = (c->fused_launches + 1) * (unsigned long long)c->f_grid;
+        if (c->fail_next && !lag) fa.barrier_target += 1;  // adascale_fail_next_barrier: an arrival that never comes
+        c->fail_next = false;
+        fa.spin_limit = c->tun.barrier_spin_limit > 0 ? c->tun.barrier_spin_limit : kFSpinLimit;
         fa.fault = c->d_fault;
         fa.n_tiles = (int)c->ftiles.size();
         fa.tiles_per_block = c->f_tpb;
@@ -827,9 +857,6 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.rho = (float)c->cfg.momentum;
         fa.lambda = (float)c->cfg.weight_decay;
         fa.sc = sa;
-#ifdef ADASCALE_FUSED_TIMING
-        HIP_TRY(c, fused_timing_hook(c, &fa));
-#endif
         void *args[] = {&fa};
         const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
         if (c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) {
@@ -861,7 +888,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
         return ADASCALE_OK;
     }
-    const int grid = std::min(c->n_spans, c->max_blocks);
+    const int grid = c->n_spans;
     const void *stream_fn = c->stream_ok ? stream_kernel_for(c->cfg.grad_dtype, S) : nullptr;
     int n_partials = c->n_spans;
     if (stream_fn) {
@@ -869,7 +896,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.tiles = c->d_ftiles;
         ra.cold = c->d_ctiles;
         ra.numel = c->d_numel;
-        ra.ptrs = c->d_ptrs;
+        ra.ptrs = d_ptrs;
         ra.partials = c->d_partials;
         ra.claim = c->d_claim + (c->stream_launches & 1);
         ra.claim_next = c->d_claim + ((c->stream_launches + 1) & 1);
@@ -893,8 +920,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     // averages and k_update applies it.
     if (lag && !stream_fn) {
         if (grid > 0) {
-            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, grid, s, S, st_in, sa);
-            else launch_reduce_update<Bf16>(c, grid, s, S, st_in, sa);
+            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, d_ptrs, grid, s, S, st_in, sa);
+            else launch_reduce_update<Bf16>(c, d_ptrs, grid, s, S, st_in, sa);
             HIP_TRY(c, hipGetLastError());
         }
         if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
@@ -907,8 +934,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         return ADASCALE_OK;
     }
     if (!stream_fn && grid > 0) {
-        if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, grid, s, S);
-        else launch_reduce<Bf16>(c, grid, s, S);
+        if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce<float>(c, d_ptrs, grid, s, S);
+        else launch_reduce<Bf16>(c, d_ptrs, grid, s, S);
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
@@ -921,11 +948,11 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
 #define LAUNCH(VV)                                                                                       \
     hipLaunchKernelGGL((k_update<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
-                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,  \
-                       lambda, c->update_reverse)
+                       c->d_numel, d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,     \
+                       lambda)
 #define LAUNCH_APPLY(VV)                                                                                    \
     hipLaunchKernelGGL((k_apply<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,  \
-                       c->d_numel, c->d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len)
+                       c->d_numel, d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len)
         if (stream_fn && c->stream_momentum) {
             if (c->vec == 4) LAUNCH_APPLY(4);
             else LAUNCH_APPLY(8);

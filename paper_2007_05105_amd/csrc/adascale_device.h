@@ -17,7 +17,7 @@
 #include <new>
 #include <vector>
 
-#include "adascale.h"
+#include "adascale_diag.h"
 
 namespace {
 
@@ -32,7 +32,7 @@ namespace {
 constexpr int kThreads = ADASCALE_THREADS;
 constexpr int kWave = 64;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kRing = 4;  // pinned staging slots for pointer-table uploads
+constexpr int kTables = 8;  // pointer tables kept on the device, each with a pinned host mirror
 
 struct DevState {
     long long step;
@@ -528,16 +528,13 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
                                                      const long long *__restrict__ numel,
                                                      const unsigned long long *__restrict__ ptrs,
                                                      const DevState *__restrict__ st, int n_tiles, int span_tiles,
-                                                     int n_spans, int row_len, float rho, float lambda,
-                                                     int reverse)
+                                                     int n_spans, int row_len, float rho, float lambda)
 {
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
     const float eta = st->eta_f32;
 
-    for (int sp = blockIdx.x; sp < n_spans; sp += gridDim.x) {
-        // reverse: start with the spans whose mean gradient was written last
-        const int span = reverse ? n_spans - 1 - sp : sp;
+    for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
         const int t0 = span * span_tiles;
         const int t1 = min(t0 + span_tiles, n_tiles);
         int k = span_first[span];
@@ -597,7 +594,7 @@ constexpr int kFWaves = kFThreads / kWave;
 constexpr int kFRegTiles = 44;                 // most f4 per lane kept in VGPRs (176 of the 256 registers)
 constexpr int kFTile = kFThreads * 4;          // elements per tile (fp32 gradients)
 constexpr int kFMaxGrid = 256;                 // workgroups (one per CU) = partial slots
-constexpr long long kFSpinLimit = 1LL << 22;   // bounded wait at the grid barrier
+constexpr long long kFSpinLimit = 1LL << 22;   // polls of the bounded wait at the grid barrier (several seconds)
 
 struct FTile {
     int k;      // tensor
@@ -843,25 +840,14 @@ struct FusedArgs {
     const float *lr;
     unsigned long long *barrier;   // monotonically increasing arrival counter
     unsigned long long barrier_target;
+    long long spin_limit;          // polls after which the wait at the barrier gives up
     int *fault;                    // set when the bounded wait at the barrier gave up
     int n_tiles, n_cold, tiles_per_block, lds_tiles, S, row_len;
     int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
     float rho, lambda;
     ScalarArgs sc;
-#ifdef ADASCALE_FUSED_TIMING
-    unsigned long long *timing;    // [gridDim.x][8] wall-clock stamps (development builds only)
-#endif
 };
-
-#ifdef ADASCALE_FUSED_TIMING
-#define FUSED_STAMP(i)                                                  \
-    do {                                                                \
-        if (tid == 0) p.timing[(size_t)b * 8 + (i)] = wall_clock64();   \
-    } while (0)
-#else
-#define FUSED_STAMP(i) do { } while (0)
-#endif
 
 // Ragged last tile of a tensor, phase 1: per-lane predicates, mean gradient to the HBM scratch.
 // Lanes wholly inside the tensor use one 16-byte load per replica, the lane on the boundary
@@ -1011,6 +997,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     extern __shared__ f4 lds_gbar[];  // [lds_tiles][kFThreads]
     __shared__ double red[kFMaxGrid][2];
     __shared__ float sh_eta;
+    __shared__ int sh_fault;
     const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
     // this workgroup's slots: full tiles b, b + G, b + 2G, ...
     const int n_valid = b < p.n_tiles ? (p.n_tiles - 1 - b) / G + 1 : 0;
@@ -1023,10 +1010,8 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     double acc_a = 0.0, acc_b = 0.0;
 
     // phase 1
-    FUSED_STAMP(0);
     // ragged tiles go to the workgroups from the top: those are the ones with one full tile less
     for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_mean<GT, HG, FusedArgs>(p, c, tid, acc_a, acc_b);
-    FUSED_STAMP(1);
 
     if (n_valid > 0) {
         typename FGrad<GT>::raw xa[HG];
@@ -1064,10 +1049,6 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     }
 
     // workgroup partial -> fixed slot
-    FUSED_STAMP(2);
-#ifdef ADASCALE_FUSED_TIMING
-    if (tid == kFThreads - 64) p.timing[(size_t)b * 8 + 7] = wall_clock64();
-#endif
     acc_a = wave_sum(acc_a);
     acc_b = wave_sum(acc_b);
     if ((tid & (kWave - 1)) == 0) {
@@ -1097,26 +1078,34 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
             __hip_atomic_store(&p.partials[(size_t)b * 2 + tid], t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __builtin_amdgcn_s_waitcnt(0);  // vmcnt(0) expcnt(0) lgkmcnt(0): the store has been acknowledged
         }
-        FUSED_STAMP(5);
 
-        // grid barrier with a bounded wait
+        // Grid barrier with a bounded wait.  A workgroup whose wait runs out raises the fault flag;
+        // every poll reads the flag beside the counter (two loads in flight, one latency), so the
+        // others stop waiting too.  A workgroup that has seen the flag leaves without evaluating the
+        // scalars and without phase 2: its retained tiles leave w and v as they were and the state
+        // record is not advanced by it.  (Workgroups that saw all arrivals before the flag went up
+        // carry on; tiles beyond the chip's capacity already hold the new momentum in v.  The host
+        // reports the step as failed either way.)
         __syncthreads();
         if (tid == 0) {
             __hip_atomic_fetch_add(p.barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             long long spins = 0;
-            bool ok = true;
-            // poll not too often: 256 pollers share one address
-            while (__hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < p.barrier_target) {
-                __builtin_amdgcn_s_sleep(16);
-                if (++spins > kFSpinLimit) {
-                    ok = false;
+            int failed = 0;
+            for (;;) {
+                const unsigned long long seen = __hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                failed = __hip_atomic_load(p.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (failed || seen >= p.barrier_target) break;
+                if (++spins > p.spin_limit) {
+                    __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    failed = 1;
                     break;
                 }
+                __builtin_amdgcn_s_sleep(16);  // poll not too often: 256 pollers share one address
             }
-            if (!ok) __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_fault = failed;
         }
         __syncthreads();
-        FUSED_STAMP(6);
+        if (sh_fault) return;
 
         // every workgroup: the same fixed-order sum of all partials, then the scalars
         for (int j = tid; j < kFMaxGrid; j += kFThreads) {
@@ -1135,9 +1124,6 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], p.st_in, p.st_out, p.lr, p.sc, b == 0);
         __syncthreads();
         eta = sh_eta;
-        FUSED_STAMP(3);
-
-
     }
     // phase 2: momentum update from the retained mean gradient
     if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
@@ -1145,7 +1131,6 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
     for (int q = q_hbm; q < n_valid; ++q) fused_tile_apply(cx.locate(q), lane_off, eta);
     for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);  // same owner as in phase 1
-    FUSED_STAMP(4);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1335,9 +1320,12 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
     finish(prev);
 }
 
-__global__ void k_set_state(DevState *st, long long step, double tau, double sbar, double mbar, long long L)
+// Also lowers the fault flag a fused step raises when its grid barrier gives up: the caller has
+// restored w, v and this state from a checkpoint.
+__global__ void k_set_state(DevState *st, long long step, double tau, double sbar, double mbar, long long L, int *fault)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
+        *fault = 0;
         st->step = step;
         st->tau = tau;
         st->sig_bar = sbar;

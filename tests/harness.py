@@ -17,7 +17,7 @@ import torch
 
 import workloads as W
 from oracle.oracle import Oracle
-from paper_2007_05105_amd import AdaScale
+from paper_2007_05105_amd import AdaScale, Tuning
 
 # Tolerances of the benchmark definition: relative error on the scalars, elementwise error on
 # w (and v) relative to the largest magnitude in the same tensor.
@@ -25,17 +25,36 @@ TOL_SCALAR = 1e-5
 TOL_W = 1e-6
 
 
+_PINNED_LIMIT = 8 << 30   # gradient sets up to this size come to the host through a pinned buffer kept per Inputs
+
+
 def grads_to_numpy(inp: W.Inputs) -> List[List[np.ndarray]]:
-    """The bit patterns of the S gradient buffers as numpy views per tensor (bf16 as uint16)."""
+    """The bit patterns of the S gradient buffers as numpy views per tensor (bf16 as uint16).
+    The views are valid until the next call for the same Inputs."""
+    S, n = inp.wl.S, inp.len_g
+    bf16 = inp.g_flat[0].dtype == torch.bfloat16
+    raw = torch.int16 if bf16 else torch.float32
+    staging = None
+    if inp.device.type == "cuda" and S * n * inp.wl.grad_bytes <= _PINNED_LIMIT:
+        staging = getattr(inp, "_host_staging", None)
+        if staging is None:
+            staging = inp._host_staging = torch.empty((S, n), dtype=raw, pin_memory=True)
     out = []
-    for i in range(inp.wl.S):
-        flat = inp.g_flat[i]
-        if flat.dtype == torch.bfloat16:
-            host = flat.view(torch.int16).cpu().numpy().view(np.uint16)
+    for i in range(S):
+        flat = inp.g_flat[i].view(raw)
+        if staging is not None:
+            staging[i].copy_(flat, non_blocking=True)
+            host = staging[i]
         else:
-            host = flat.cpu().numpy()
-        out.append([host[o:o + n] for n, o in zip(inp.wl.numel, inp.offs_g)])
-    return out
+            host = flat.cpu()
+        out.append(host)
+    if staging is not None:
+        torch.cuda.synchronize()
+    views = []
+    for host in out:
+        a = host.numpy().view(np.uint16) if bf16 else host.numpy()
+        views.append([a[o:o + k] for k, o in zip(inp.wl.numel, inp.offs_g)])
+    return views
 
 
 def params_to_numpy64(inp: W.Inputs):
@@ -64,6 +83,7 @@ class StepReport:
 @dataclass
 class RunReport:
     steps: List[StepReport] = field(default_factory=list)
+    free: Optional[dict] = None     # free-running oracle beside the run: final scalar errors and drift of w
 
     def worst(self) -> Dict[str, float]:
         out: Dict[str, float] = {}
@@ -73,9 +93,14 @@ class RunReport:
         return out
 
 
-def make_gpu(wl: W.Workload, device: int = 0, flags: int = 0) -> AdaScale:
+# Knobs every context made here is created with (None: the library's own choices).  The parity
+# tests set it to run each case on each of the three implementations of the step.
+DEFAULT_TUNING: Optional[Tuning] = None
+
+
+def make_gpu(wl: W.Workload, device: int = 0, flags: int = 0, tuning: Optional[Tuning] = None) -> AdaScale:
     return AdaScale(wl.numel, wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps,
-                    wl.grad_dtype, device, flags)
+                    wl.grad_dtype, device, flags, tuning=tuning if tuning is not None else DEFAULT_TUNING)
 
 
 def make_oracle(wl: W.Workload, flags: int = 0, openmp: bool = False) -> Oracle:
@@ -123,19 +148,37 @@ def tensor_err(gpu_flat: torch.Tensor, ref: List[np.ndarray], before: List[np.nd
 def run_teacher_forced(wl: W.Workload, check_steps: Optional[Iterable[int]] = None, n_steps: Optional[int] = None,
                        openmp: bool = False, flags: int = 0, skew_elems: int = 0, device: str = "cuda:0",
                        inputs: Optional[W.Inputs] = None, step_ids: Optional[Iterable[int]] = None,
-                       log=None) -> RunReport:
+                       log=None, poison: bool = False, free_oracle: bool = False) -> RunReport:
     """step_ids: which iterations' gradients to feed, in order (default 0 .. n_steps-1); all of
-    check_steps (default: every fed step) are compared with the oracle."""
+    check_steps (default: every fed step) are compared with the oracle.
+    poison: the padding of the flat buffers holds NaNs (see workloads.Inputs); after every step the
+    padding of w and v must be intact and the gradient allocations unchanged bit for bit.
+    free_oracle: a second oracle that never sees the GPU's state runs beside the teacher-forced one
+    (every fed step must then be a checked one); its final comparison is left in rep.free."""
     ids = list(range(wl.steps if n_steps is None else n_steps)) if step_ids is None else list(step_ids)
     check = set(ids) if check_steps is None else set(check_steps)
-    inp = inputs if inputs is not None else W.Inputs(wl, device, skew_elems=skew_elems)
+    inp = inputs if inputs is not None else W.Inputs(wl, device, skew_elems=skew_elems, poison=poison)
     gpu = make_gpu(wl, flags=flags)
     orc = make_oracle(wl, flags=flags, openmp=openmp)
     rep = RunReport()
+    free = None
+    if free_oracle:
+        assert check >= set(ids)
+        free = make_oracle(wl, flags=flags, openmp=openmp)
+        wf, vf = params_to_numpy64(inp)
+        w_start = [x.copy() for x in wf]
     for t in ids:
         inp.fill_grads(t)
+        g_bits = inp.grad_bits() if inp.poison else None
+
+        def check_padding():
+            if inp.poison:
+                assert inp.padding_intact(), f"step {t}: something wrote between the tensors of w or v"
+                assert all(torch.equal(a, b) for a, b in zip(g_bits, inp.grad_bits())), f"step {t}: gradient buffers changed"
+
         if t not in check:
             gpu.step(inp.w, inp.v, inp.g)
+            check_padding()
             continue
         before = gpu.get_state()
         w64, v64 = params_to_numpy64(inp)
@@ -143,8 +186,12 @@ def run_teacher_forced(wl: W.Workload, check_steps: Optional[Iterable[int]] = No
         v_before = [x.copy() for x in v64]
         gpu.step(inp.w, inp.v, inp.g)
         after = gpu.get_state()
+        check_padding()
         orc.set_state(before.step, before.tau, before.sigma2_bar, before.mu2_bar, before.r)
-        ost = orc.step(w64, v64, grads_to_numpy(inp))
+        g_np = grads_to_numpy(inp)
+        ost = orc.step(w64, v64, g_np)
+        if free is not None:
+            fst = free.step(wf, vf, g_np)
         sr = StepReport(t, compare_step(after, ost, wl.S),
                         tensor_err(inp.w_flat, w64, w_before, wl.numel, inp.offs32),
                         tensor_err(inp.v_flat, v64, v_before, wl.numel, inp.offs32), ost.r, ost.tau)
@@ -154,6 +201,9 @@ def run_teacher_forced(wl: W.Workload, check_steps: Optional[Iterable[int]] = No
             log(f"step {t}: r={ost.r:.6g} tau={ost.tau:.6g} worst_scalar={graded:.3g} "
                 f"(plain rel. error of sigma2_hat {sr.rel['sigma2_hat_plain']:.3g}, mu2_hat {sr.rel['mu2_hat_plain']:.3g}) "
                 f"w_err={sr.w_err:.3g} v_err={sr.v_err:.3g}")
+    if free is not None:
+        rep.free = {"rel": compare_step(gpu.get_state(), fst, wl.S),
+                    "w_drift": tensor_err(inp.w_flat, wf, w_start, wl.numel, inp.offs32), "steps": len(ids)}
     gpu.close()
     return rep
 

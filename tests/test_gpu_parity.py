@@ -12,8 +12,8 @@ import torch
 
 import harness as H
 import workloads as W
-from paper_2007_05105_amd import (BF16, COOPERATIVE_LAUNCH, EST_NORM_RATIO, F32, LAGGED_R, NO_POINTER_CHECK,
-                                  AdaScale, AdaScaleError)
+from paper_2007_05105_amd import (BF16, COOPERATIVE_LAUNCH, EST_NORM_RATIO, F32, FORCE_FUSED, FORCE_GENERAL,
+                                  FORCE_STREAMING, LAGGED_R, NO_POINTER_CHECK, AdaScale, AdaScaleError, Tuning)
 
 pytestmark = pytest.mark.gpu
 
@@ -29,9 +29,8 @@ def step_path(request, monkeypatch):
     it fits), the three-kernel step with the streaming reduce kernel (what parameter lists far
     larger than the chip get), and the general three-kernel step (any scale; the other two stop
     at S = 4096)."""
-    monkeypatch.setenv("ADASCALE_FUSED", "1" if request.param == "fused" else "2")
-    monkeypatch.setenv("ADASCALE_STREAM", "2" if request.param == "general" else "1")
-    monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
+    force = {"fused": FORCE_FUSED, "three_kernel": FORCE_STREAMING, "general": FORCE_GENERAL}[request.param]
+    monkeypatch.setattr(H, "DEFAULT_TUNING", Tuning(force_path=force))
     return request.param
 
 
@@ -64,8 +63,7 @@ def test_fused_step_spills_to_hbm_when_the_chip_is_full(S, dtype, step_path, mon
     momentum in place and phase 2 only applies it."""
     if step_path != "fused":
         pytest.skip("fused step only")
-    monkeypatch.setenv("ADASCALE_FUSED_GRID", "2")
-    monkeypatch.setenv("ADASCALE_FUSED_MIN_PCT", "1")
+    monkeypatch.setattr(H, "DEFAULT_TUNING", Tuning(force_path=FORCE_FUSED, fused_max_grid=2))
     wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5,
                   steps=3, seed=S)
     g = H.make_gpu(wl)
@@ -109,7 +107,7 @@ def test_empty_tensors_and_empty_list():
     """numel 0 tensors are skipped; an empty parameter list still advances the clock."""
     wl = W.custom([(0,), (300,), (0,), (0,), (5,)], 3, steps=2, seed=9)
     H.assert_report(H.run_teacher_forced(wl, log=log))
-    g = AdaScale([], 4, [0.1], theta=0.0)
+    g = AdaScale([], 4, [0.1], theta=0.0, tuning=H.DEFAULT_TUNING)
     assert not g.uses_fused_step()
     g.step([], [], [[], [], [], []])
     st = g.get_state()
@@ -177,6 +175,116 @@ def test_two_contexts_on_two_streams(step_path):
     a, b = run(False), run(True)
     for (sa, wa), (sb, wb) in zip(a, b):
         assert sa == sb and torch.equal(wa, wb)
+
+
+# ------------------------------------------------------------ nothing outside the tensors
+@pytest.mark.parametrize("skew", [0, 1, 3])
+@pytest.mark.parametrize("S,dtype,flags", [(4, F32, 0), (5, F32, 0), (4, BF16, 0), (11, BF16, 0), (16, F32, LAGGED_R),
+                                           (6, BF16, LAGGED_R)])
+def test_poisoned_padding_is_neither_read_nor_written(skew, S, dtype, flags):
+    """Every element between the tensors (and between the gradient rows) holds a NaN: an
+    out-of-extent read at a ragged tail would put it into A or B, an out-of-extent write would
+    replace the sentinel in w or v (checked bit for bit after every step, with the gradient
+    buffers, which the library must never write)."""
+    wl = W.custom(SMALL_SHAPES, S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5, steps=3, seed=50 + S)
+    rep = H.run_teacher_forced(wl, skew_elems=skew, flags=flags, poison=True, log=log)
+    H.assert_report(rep)
+
+
+@pytest.mark.parametrize("skew", [0, 1])
+@pytest.mark.parametrize("S,dtype", [(3, F32), (16, F32), (8, BF16), (33, BF16)])
+def test_poisoned_padding_with_tiles_beyond_the_chip(skew, S, dtype, step_path, monkeypatch):
+    """The same with two workgroups only, so that most tiles take the momentum-in-the-sweep path of
+    the fused step, and on the streaming kernel's many pairs per workgroup."""
+    if step_path == "fused":
+        monkeypatch.setattr(H, "DEFAULT_TUNING", Tuning(force_path=FORCE_FUSED, fused_max_grid=2))
+    wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5,
+                  steps=2, seed=60 + S)
+    H.assert_report(H.run_teacher_forced(wl, skew_elems=skew, poison=True, log=log))
+
+
+# ---------------------------------------------------------------- pointer sets and failure
+def test_alternating_pointer_sets(step_path):
+    """A caller that rotates between three (w, v) pairs and two sets of gradient buffers (six
+    distinct pointer sets, more than the library keeps tables for) gets bit for bit what a caller
+    with one fixed set of buffers gets when the same data is copied in and out of them."""
+    wl = W.custom([(70000,), (513,), (4096, 3)], 4, weight_decay=1e-3, theta=0.5, lr_table=W.lr_step_decay(0.1, 16),
+                  steps=12, seed=71)
+    sets = [W.Inputs(wl, "cuda:0") for _ in range(3)]
+    for j, inp in enumerate(sets):
+        inp.w_flat.mul_(1.0 + j)
+    gsets = [W.Inputs(wl, "cuda:0"), W.Inputs(wl, "cuda:0")]
+    gsets[0].fill_grads(0)
+    gsets[1].fill_grads(1)
+    start = [(inp.w_flat.clone(), inp.v_flat.clone()) for inp in sets]
+
+    rot = H.make_gpu(wl)
+    for t in range(wl.steps):
+        rot.step(sets[t % 3].w, sets[t % 3].v, gsets[t % 2].g)
+    st_rot = rot.get_state().as_dict()
+    rot.close()
+    got = [(inp.w_flat.clone(), inp.v_flat.clone()) for inp in sets]
+
+    fixed = W.Inputs(wl, "cuda:0")
+    cur = [(w.clone(), v.clone()) for w, v in start]
+    one = H.make_gpu(wl)
+    for t in range(wl.steps):
+        fixed.w_flat.copy_(cur[t % 3][0])
+        fixed.v_flat.copy_(cur[t % 3][1])
+        for dst, src in zip(fixed.g_flat, gsets[t % 2].g_flat):
+            dst.copy_(src)
+        one.step(fixed.w, fixed.v, fixed.g)
+        cur[t % 3] = (fixed.w_flat.clone(), fixed.v_flat.clone())
+    st_one = one.get_state().as_dict()
+    one.close()
+    assert st_rot == st_one
+    for (w1, v1), (w2, v2) in zip(got, cur):
+        assert torch.equal(w1, w2) and torch.equal(v1, v2)
+
+
+@pytest.mark.parametrize("flags", [0, COOPERATIVE_LAUNCH])
+def test_grid_barrier_that_gives_up_is_reported_and_recoverable(flags, step_path):
+    """The failure path of the fused step, forced from the host: the barrier of one step waits for
+    an arrival that never comes, with a wait of a few hundred polls, so every workgroup gives up
+    and every kernel exits normally.  The step must leave w and v alone (all tiles are on chip
+    here), adascale_get_state and further steps must report ESTATE, and after adascale_set_state
+    the run continues exactly like one that never failed."""
+    if step_path != "fused":
+        pytest.skip("fused step only")
+    wl = W.custom([(300000,), (999,), (5000,)], 8, weight_decay=1e-3, theta=0.5, steps=3, seed=21)
+    tun = Tuning(force_path=FORCE_FUSED, barrier_spin_limit=300)
+
+    def run(fail_at):
+        inp = W.Inputs(wl, "cuda:0")
+        g = H.make_gpu(wl, flags=flags, tuning=tun)
+        for t in range(wl.steps):
+            inp.fill_grads(t)
+            if t == fail_at:
+                st = g.get_state()
+                w0, v0 = inp.w_flat.clone(), inp.v_flat.clone()
+                g.fail_next_barrier()
+                g.step(inp.w, inp.v, inp.g)                     # queued; the failure shows at the next query
+                with pytest.raises(AdaScaleError) as e:
+                    g.get_state()
+                assert e.value.code == 4
+                assert torch.equal(inp.w_flat, w0) and torch.equal(inp.v_flat, v0)
+                with pytest.raises(AdaScaleError) as e:
+                    g.step(inp.w, inp.v, inp.g)
+                assert e.value.code == 4
+                g.set_state(st.step, st.tau, st.sigma2_bar, st.mu2_bar)
+            g.step(inp.w, inp.v, inp.g)
+        out = (g.get_state().as_dict(), inp.w_flat.clone(), inp.v_flat.clone())
+        g.close()
+        return out
+
+    a, b = run(None), run(1)
+    assert a[0] == b[0] and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+    # a context without a barrier has nothing to fail
+    g = H.make_gpu(wl, flags=LAGGED_R, tuning=tun)
+    with pytest.raises(AdaScaleError) as e:
+        g.fail_next_barrier()
+    assert e.value.code == 4
+    g.close()
 
 
 def test_free_running_small():
@@ -338,7 +446,7 @@ def test_error_paths_launch_nothing():
         AdaScale([-1], 2, [0.1])
     with pytest.raises(AdaScaleError):
         AdaScale([10], 2, [])
-    g = AdaScale([1000], 2, [0.1])
+    g = AdaScale([1000], 2, [0.1], tuning=H.DEFAULT_TUNING)
     w = torch.zeros(1000, device="cuda:0")
     v = torch.zeros(1000, device="cuda:0")
     ok = [torch.ones(1000, device="cuda:0"), torch.ones(1000, device="cuda:0")]
@@ -367,9 +475,7 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
     kernel beyond (cfg5: 9 %)."""
     if step_path != "fused":
         pytest.skip("one run is enough")
-    monkeypatch.delenv("ADASCALE_FUSED")
-    monkeypatch.delenv("ADASCALE_FUSED_MIN_PCT")
-    monkeypatch.delenv("ADASCALE_STREAM")
+    monkeypatch.setattr(H, "DEFAULT_TUNING", None)
     import torch
     from paper_2007_05105_amd import binding
     prop = torch.cuda.get_device_properties(0)
@@ -377,6 +483,15 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
         wl = W.config(cfg)
         g = H.make_gpu(wl)
         assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
+        # bytes the kernels move, against a count in Python: on-chip tiles 16 per parameter, tiles whose
+        # sweep leaves the momentum in v 20 (24 with weight decay), ragged tiles through the scratch
+        full = sum(n // 2048 * 2048 for n in wl.numel)
+        keep = {1: 1.0, 2: 1.0, 3: 1.0, 5: 0.0}.get(cfg)
+        if keep is not None:
+            per = 16 if keep else (24 if wl.weight_decay else 20)
+            ragged = 24 if path == "fused" else 32
+            assert g.step_moved_bytes() == wl.S * wl.d * wl.grad_bytes + per * full + ragged * (wl.d - full), cfg
+        assert g.step_moved_bytes() <= g.step_bytes() + 12 * (wl.d - full)
         # the host-only plan for a device of this size says the same
         plan = binding.plan(wl.numel, wl.S, wl.grad_dtype, compute_units=prop.multi_processor_count,
                             lds_bytes=prop.shared_memory_per_block)

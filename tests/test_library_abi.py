@@ -11,8 +11,8 @@ from paper_2007_05105_amd import binding
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "adascale.h")).read()
+def declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(adascale_[a-z_]+)\s*\(", text)))
 
@@ -21,11 +21,23 @@ def test_library_exports_every_declared_symbol():
     if not os.path.exists(binding.library_path()):
         pytest.skip("libadascale.so not built (run __graft_entry__.build())")
     lib = C.CDLL(binding.library_path())
-    names = declared_symbols()
-    assert len(names) >= 8
-    for n in names:
-        assert hasattr(lib, n), n
-    assert sorted(binding.EXPORTS) == names      # the Python binding carries the same names
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["adascale.h", "adascale_diag.h"]
+    for header, exports in (("adascale.h", binding.EXPORTS), ("adascale_diag.h", binding.EXPORTS_DIAG)):
+        names = declared_symbols(header)
+        assert len(names) >= 7
+        for n in names:
+            assert hasattr(lib, n), n
+        assert sorted(exports) == names          # the Python binding carries the same names
+
+
+def test_library_reads_no_environment_variables():
+    """What a call does depends on its arguments alone: the library does not import getenv."""
+    import subprocess
+    if not os.path.exists(binding.library_path()):
+        pytest.skip("libadascale.so not built")
+    out = subprocess.run(["nm", "-D", "--undefined-only", binding.library_path()], capture_output=True, text=True,
+                         check=True).stdout
+    assert "getenv" not in out
 
 
 def test_struct_layouts_match_header(tmp_path):
@@ -35,11 +47,14 @@ def test_struct_layouts_match_header(tmp_path):
     fields_c = [n for n, _ in binding.Config._fields_]
     fields_s = [n for n, _ in binding.State._fields_]
     fields_p = [n for n, _ in binding.PlanInfo._fields_]
+    fields_t = [n for n, _ in binding.Tuning._fields_]
     body = "".join(f'printf("%zu\\n", offsetof(adascale_config, {f}));' for f in fields_c)
     body += "".join(f'printf("%zu\\n", offsetof(adascale_state, {f}));' for f in fields_s)
     body += "".join(f'printf("%zu\\n", offsetof(adascale_plan_info, {f}));' for f in fields_p)
     body += 'printf("%zu\\n", sizeof(adascale_plan_info));'
-    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "adascale.h"\nint main(void){'
+    body += "".join(f'printf("%zu\\n", offsetof(adascale_tuning, {f}));' for f in fields_t)
+    body += 'printf("%zu\\n", sizeof(adascale_tuning));'
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "adascale_diag.h"\nint main(void){'
                    'printf("%zu\\n%zu\\n", sizeof(adascale_config), sizeof(adascale_state));' + body + "return 0;}")
     exe = tmp_path / "layout"
     subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
@@ -47,6 +62,7 @@ def test_struct_layouts_match_header(tmp_path):
     assert out[0] == C.sizeof(binding.Config) and out[1] == C.sizeof(binding.State)
     got = [getattr(binding.Config, f).offset for f in fields_c] + [getattr(binding.State, f).offset for f in fields_s]
     got += [getattr(binding.PlanInfo, f).offset for f in fields_p] + [C.sizeof(binding.PlanInfo)]
+    got += [getattr(binding.Tuning, f).offset for f in fields_t] + [C.sizeof(binding.Tuning)]
     assert out[2:] == got
 
 
@@ -84,15 +100,13 @@ def test_every_scale_up_to_4096_has_a_kernel_shape_and_instances():
     assert binding.kernel_shape(1, 64)[1] == (8, 8, 64)
 
 
-def test_plan_of_the_benchmark_configurations(monkeypatch):
+def test_plan_of_the_benchmark_configurations():
     """Host logic that lays a parameter list out over the chip (no device needed): tile counts
     against a count in Python, the split of the mean gradient between registers, LDS and memory,
     and the path, for the five workloads on an MI355X-sized device."""
     if not os.path.exists(binding.library_path()):
         pytest.skip("libadascale.so not built")
     import workloads as W
-    for name in ("ADASCALE_FUSED", "ADASCALE_STREAM", "ADASCALE_FUSED_MIN_PCT", "ADASCALE_FUSED_GRID"):
-        monkeypatch.delenv(name, raising=False)
     expect = {1: "fused", 2: "fused", 3: "fused", 4: "fused", 5: "streaming"}
     for cfg in range(1, 6):
         wl = W.config(cfg)
@@ -113,17 +127,24 @@ def test_plan_of_the_benchmark_configurations(monkeypatch):
     p3, p4 = binding.plan(W.config(3).numel, 16), binding.plan(W.config(4).numel, 32, binding.BF16)
     assert (p3["register_tiles"], p3["on_chip_percent"]) == (44, 100)
     assert (p4["register_tiles"], p4["lds_tiles"], p4["tiles_per_workgroup"], p4["on_chip_percent"]) == (44, 19, 116, 54)
-    # scales beyond the 512-lane kernels' range, an empty list, and the environment switches
+    # scales beyond the 512-lane kernels' range, an empty list, and the knobs of the tuning record
     assert binding.plan(W.config(3).numel, 5000)["path"] == "general"
     assert binding.plan([], 4) == dict(binding.plan([0, 0], 4), path="general")
     assert binding.plan([7], 4)["ragged_tiles"] == 1 and binding.plan([7], 4)["fused_grid"] == 1
-    monkeypatch.setenv("ADASCALE_FUSED", "2")
-    assert binding.plan(W.config(3).numel, 16)["path"] == "streaming"
-    monkeypatch.setenv("ADASCALE_STREAM", "2")
-    assert binding.plan(W.config(3).numel, 16)["path"] == "general"
-    monkeypatch.delenv("ADASCALE_FUSED")
-    assert binding.plan(W.config(5).numel, 64, binding.BF16)["path"] == "fused"        # no streaming kernel to prefer
-    monkeypatch.delenv("ADASCALE_STREAM")
+    T = binding.Tuning
+    assert binding.plan(W.config(3).numel, 16, tuning=T(force_path=binding.FORCE_STREAMING))["path"] == "streaming"
+    assert binding.plan(W.config(3).numel, 16, tuning=T(force_path=binding.FORCE_GENERAL))["path"] == "general"
+    forced = binding.plan(W.config(5).numel, 64, binding.BF16, tuning=T(force_path=binding.FORCE_FUSED))
+    assert forced["path"] == "fused" and forced["on_chip_percent"] < 20
+    assert binding.plan(W.config(4).numel, 32, binding.BF16, tuning=T(fused_min_percent=60))["path"] == "streaming"
+    assert binding.plan(W.config(5).numel, 64, binding.BF16, tuning=T(fused_min_percent=5))["path"] == "fused"
+    few = binding.plan(W.config(1).numel, 4, tuning=T(fused_max_grid=2))
+    assert few["fused_grid"] == 2 and few["tiles_per_workgroup"] == 244 and few["register_tiles"] + few["lds_tiles"] == 63
+    os.environ["ADASCALE_FUSED"] = "2"              # the library does not read the environment
+    try:
+        assert binding.plan(W.config(3).numel, 16)["path"] == "fused"
+    finally:
+        del os.environ["ADASCALE_FUSED"]
     # a device with a quarter of the compute units keeps a quarter of the parameters on chip
     small = binding.plan(W.config(3).numel, 16, compute_units=64)
     assert small["fused_grid"] == 64 and small["on_chip_percent"] == 100 * 63 // small["tiles_per_workgroup"]

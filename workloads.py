@@ -232,11 +232,19 @@ class Inputs:
     both consumers read the same bits out of these buffers.
     """
 
+    # What `poison` puts into every element of the flat buffers that belongs to no tensor: a NaN
+    # with this bit pattern in w and v, plain NaNs in the gradient buffers.
+    SENTINEL_BITS = 0x7FC0ABCD
+
     def __init__(self, wl: Workload, device: str | torch.device = "cpu", skew_elems: int = 0,
-                 one_allocation: bool = True):
+                 one_allocation: bool = True, poison: bool = False):
         """`one_allocation`: the S gradient buffers are rows of one [S, length] allocation, the
-        layout a gathered set of per-replica gradients has (False: one allocation per replica)."""
+        layout a gathered set of per-replica gradients has (False: one allocation per replica).
+        `poison`: the elements between tensors (and between gradient rows) hold NaNs instead of
+        zeros, so a consumer that reads outside a tensor's extent gets a NaN into its sums, and
+        `padding_intact()` tells whether one has written there."""
         self.wl, self.device = wl, torch.device(device)
+        self.poison = poison
         self.offs32, self.len32 = layout(wl.numel, 4, skew_elems=skew_elems)
         self.offs_g, self.len_g = layout(wl.numel, wl.grad_bytes, skew_elems=skew_elems)
         dev = self.device
@@ -251,11 +259,16 @@ class Inputs:
             nbytes = self.len_g * wl.grad_bytes
             a = _ROW_ALIGN_BYTES if nbytes >= _ROW_ALIGN_BYTES else _ALIGN_BYTES
             row = (nbytes + a - 1) // a * a // wl.grad_bytes
-            self.g_all = torch.zeros(max(1, wl.S * row), dtype=wl.torch_grad_dtype(), device=dev)
+            self.g_all = torch.full((max(1, wl.S * row),), float("nan") if poison else 0.0,
+                                    dtype=wl.torch_grad_dtype(), device=dev)
             self.g_flat = [self.g_all[i * row: i * row + self.len_g] for i in range(wl.S)]
         else:
             self.g_flat = [torch.zeros(self.len_g, dtype=wl.torch_grad_dtype(), device=dev)
                            for _ in range(wl.S)]
+        if poison:
+            pad = self._pad_mask32() == 0
+            self.w_flat.view(torch.int32)[pad] = self.SENTINEL_BITS
+            self.v_flat.view(torch.int32)[pad] = self.SENTINEL_BITS
         self.w = views(self.w_flat, wl.numel, self.offs32)
         self.v = views(self.v_flat, wl.numel, self.offs32)
         self.g = [views(f, wl.numel, self.offs_g) for f in self.g_flat]
@@ -337,14 +350,33 @@ class Inputs:
                 self.g_flat[i].zero_()
         else:
             raise ValueError(f"unknown recipe {rec}")
-        # padding between tensors stays zero so that flat-buffer consumers see no garbage
+        # padding between tensors: zero, so that flat-buffer consumers see no garbage -- or, with
+        # `poison`, NaN, so that a read outside a tensor's extent shows in the consumer's sums
         if self.len_g != wl.d:
             mask = self._pad_mask()
             for i in range(wl.S):
                 self.g_flat[i].mul_(mask.to(self.g_flat[i].dtype))
+                if self.poison:
+                    self.g_flat[i][mask == 0] = float("nan")
 
     def _pad_mask(self) -> torch.Tensor:
         if not hasattr(self, "_mask"):
             self._mask = _fill_by_tensor(self.wl, self.offs_g, self.len_g,
                                          np.ones(self.wl.n_tensors), self.device)
         return self._mask
+
+    def _pad_mask32(self) -> torch.Tensor:
+        if not hasattr(self, "_mask32"):
+            self._mask32 = _fill_by_tensor(self.wl, self.offs32, self.len32,
+                                           np.ones(self.wl.n_tensors), self.device)
+        return self._mask32
+
+    def grad_bits(self) -> List[torch.Tensor]:
+        """Copies of the gradient allocations as raw integers (to check that nobody wrote to them)."""
+        bufs = [self.g_all] if hasattr(self, "g_all") else self.g_flat
+        return [b.view(torch.int32 if b.dtype == torch.float32 else torch.int16).clone() for b in bufs]
+
+    def padding_intact(self) -> bool:
+        """With `poison`: does every element of w and v outside the tensors still hold the sentinel?"""
+        pad = self._pad_mask32() == 0
+        return all(bool((f.view(torch.int32)[pad] == self.SENTINEL_BITS).all()) for f in (self.w_flat, self.v_flat))
