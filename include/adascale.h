@@ -162,6 +162,44 @@ int adascale_set_state(adascale_ctx *ctx, int64_t step, double tau, double sigma
  */
 int adascale_set_scale(adascale_ctx *ctx, int32_t S_new, double theta);
 
+/*
+ * One AdaScale iteration on a single flat parameter tensor, for callers that cannot allocate
+ * device memory or keep a context: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  No context: everything comes in the argument record, and the call
+ * allocates nothing on the host or the device (no hipMalloc, hipFree or any call that does).
+ * What its kernels need beyond the caller's buffers (pointer row, state records, partial sums)
+ * lies in a fixed block of about 34 KB of device memory inside the library's image, one per GPU,
+ * held until the process ends.  Consequences:
+ *   - at most ADASCALE_FLAT_MAX_SCALE gradient buffers and ADASCALE_FLAT_MAX_NUMEL elements;
+ *     anything beyond is ADASCALE_EINVAL with a message (adascale_last_error(NULL));
+ *   - all calls on one GPU share that block: calls that may overlap on one GPU (different
+ *     streams or threads of one process; another process has its own copy) race; issue them on
+ *     one stream, or order the streams with events;
+ *   - the first call on each device looks up the block's address (hipGetSymbolAddress); make that
+ *     call outside graph capture.
+ * It computes what adascale_step computes for a context with this one tensor (same readings,
+ * same flags LAGGED_R / EST_NORM_RATIO / NO_POINTER_CHECK), as a gradient sweep that leaves the new
+ * momentum in `mom`, the scalar kernel, and w <- w - eta_t mom; results agree with adascale_step
+ * to rounding (the sums are taken in another order).  Asynchronous on hip_stream.
+ */
+#define ADASCALE_FLAT_MAX_SCALE 64
+#define ADASCALE_FLAT_MAX_NUMEL (((int64_t)1 << 40) - 1)
+typedef struct {
+    int32_t S;               /* 1 .. ADASCALE_FLAT_MAX_SCALE */
+    int32_t grad_dtype;      /* ADASCALE_F32 or ADASCALE_BF16 */
+    int64_t numel;           /* 0 .. ADASCALE_FLAT_MAX_NUMEL */
+    double momentum, weight_decay, theta, eps;   /* as in adascale_config */
+    uint32_t flags;          /* ADASCALE_LAGGED_R | ADASCALE_EST_NORM_RATIO | ADASCALE_NO_POINTER_CHECK */
+    int32_t device;          /* HIP device ordinal of every pointer below */
+    void *w, *mom;           /* DEVICE fp32 [numel], updated in place */
+    const void *const *grads; /* HOST array [S] of DEVICE pointers to [numel] elements of grad_dtype; read only */
+    const float *lr_table;   /* DEVICE [lr_table_len]: lr(0..L-1) */
+    int64_t lr_table_len;
+    adascale_state *state;   /* DEVICE record, 8-byte aligned, read (step, tau, sigma2_bar, mu2_bar) and
+                                rewritten whole; zero-filled = start of a run */
+} adascale_flat_step;
+int adascale_step_flat(const adascale_flat_step *args, void *hip_stream);
+
 /* Free the context and its device scratch.  Waits for the device to go idle.  NULL is allowed. */
 void adascale_destroy(adascale_ctx *ctx);
 

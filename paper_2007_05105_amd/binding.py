@@ -21,7 +21,7 @@ FORCE_NONE, FORCE_GENERAL, FORCE_FUSED, FORCE_STREAMING = 0, 1, 2, 3
 
 # adascale.h: the interface of the method
 EXPORTS = ["adascale_init", "adascale_step", "adascale_get_state", "adascale_set_state",
-           "adascale_set_scale", "adascale_destroy", "adascale_last_error"]
+           "adascale_set_scale", "adascale_destroy", "adascale_last_error", "adascale_step_flat"]
 # adascale_diag.h: diagnostics, instrumentation, test knobs
 EXPORTS_DIAG = ["adascale_step_bytes", "adascale_step_moved_bytes", "adascale_profile_begin", "adascale_profile_end",
                 "adascale_uses_fused_step", "adascale_step_path", "adascale_kernel_shape", "adascale_plan",
@@ -49,6 +49,18 @@ class State(C.Structure):
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class FlatStep(C.Structure):
+    """adascale_flat_step: the argument record of adascale_step_flat."""
+    _fields_ = [("S", C.c_int32), ("grad_dtype", C.c_int32), ("numel", C.c_int64), ("momentum", C.c_double),
+                ("weight_decay", C.c_double), ("theta", C.c_double), ("eps", C.c_double), ("flags", C.c_uint32),
+                ("device", C.c_int32), ("w", C.c_void_p), ("mom", C.c_void_p), ("grads", C.POINTER(C.c_void_p)),
+                ("lr_table", C.c_void_p), ("lr_table_len", C.c_int64), ("state", C.c_void_p)]
+
+
+FLAT_MAX_SCALE = 64
+FLAT_MAX_NUMEL = (1 << 40) - 1
 
 
 class Tuning(C.Structure):
@@ -110,6 +122,8 @@ def load_library() -> C.CDLL:
         lib.adascale_kernel_shape.restype = C.c_int
         lib.adascale_plan.argtypes = [C.POINTER(Config), C.POINTER(Tuning), C.c_int32, C.c_int64, C.POINTER(PlanInfo)]
         lib.adascale_plan.restype = C.c_int
+        lib.adascale_step_flat.argtypes = [C.POINTER(FlatStep), C.c_void_p]
+        lib.adascale_step_flat.restype = C.c_int
         lib.adascale_init_tuned.argtypes = [C.POINTER(Config), C.POINTER(Tuning), C.POINTER(C.c_void_p)]
         lib.adascale_init_tuned.restype = C.c_int
         lib.adascale_fail_next_barrier.argtypes = [C.c_void_p]
@@ -142,6 +156,26 @@ def plan(numel: Sequence[int], S: int, grad_dtype: int = F32, flags: int = 0, co
     d = info.as_dict()
     d["path"] = ("general", "fused", "streaming")[d["path"]]
     return d
+
+
+def step_flat(w, mom, grads: Sequence, lr_table_dev, state_dev, momentum: float = 0.9, weight_decay: float = 0.0,
+              theta: float = -1.0, eps: float = 1e-6, grad_dtype: int = F32, flags: int = 0, device: int = 0,
+              stream=None, numel: Optional[int] = None) -> None:
+    """adascale_step_flat: one iteration on one flat tensor with nothing allocated.  w, mom: fp32
+    device tensors; grads: S device tensors; lr_table_dev: fp32 device tensor; state_dev: device
+    tensor of at least sizeof(adascale_state) bytes holding the state record (zeros = fresh run)."""
+    lib = load_library()
+    n = int(w.numel()) if numel is None else int(numel)
+    ptrs = (C.c_void_p * len(grads))(*[int(g.data_ptr()) for g in grads])
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    args = FlatStep(len(grads), grad_dtype, n, momentum, weight_decay, theta, eps, flags, device,
+                    int(w.data_ptr()), int(mom.data_ptr()), ptrs, int(lr_table_dev.data_ptr()),
+                    int(lr_table_dev.numel()), int(state_dev.data_ptr()))
+    rc = lib.adascale_step_flat(C.byref(args), C.c_void_p(int(getattr(stream, "cuda_stream", stream))))
+    if rc != 0:
+        raise AdaScaleError(rc, lib.adascale_last_error(None).decode())
 
 
 def _ptr_array(tensors: Sequence) -> "C.Array":

@@ -46,6 +46,18 @@ FusedChain g_chain[kMaxDevices];
 
 }  // namespace
 
+// Device memory of adascale_step_flat, the entry point that allocates nothing: one block per GPU,
+// held from the moment the library is loaded until the process ends.  In host code this name is
+// only a handle for hipGetSymbolAddress (flat_scratch_on); kernels get the address it returns.
+static __device__ __align__(256) unsigned char scratch[(sizeof(FlatScratch) + 255) / 256 * 256];
+
+namespace {
+
+std::mutex g_flat_mutex;
+FlatScratch *g_flat_scratch[kMaxDevices] = {};  // address of `scratch` on each device, looked up once
+
+}  // namespace
+
 // ---------------------------------------------------------------------------------------------
 struct adascale_ctx {
     adascale_config cfg{};
@@ -965,6 +977,93 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));
+    return ADASCALE_OK;
+}
+
+// Address of this device's copy of `scratch` (the device must be current).
+static hipError_t flat_scratch_on(int device, FlatScratch **out)
+{
+    std::lock_guard<std::mutex> lock(g_flat_mutex);
+    if (!g_flat_scratch[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_flat_scratch[device] = static_cast<FlatScratch *>(p);
+    }
+    *out = g_flat_scratch[device];
+    return hipSuccess;
+}
+
+int adascale_step_flat(const adascale_flat_step *a, void *hip_stream)
+{
+    if (!a) return fail(nullptr, ADASCALE_EINVAL, "null argument record");
+    if (a->S < 1 || a->S > kFlatMaxScale)
+        return fail(nullptr, ADASCALE_EINVAL, "adascale_step_flat takes 1 to %d gradient buffers, got %d", kFlatMaxScale, a->S);
+    if (a->numel < 0 || a->numel > ADASCALE_FLAT_MAX_NUMEL)
+        return fail(nullptr, ADASCALE_EINVAL, "adascale_step_flat takes at most %lld elements", (long long)ADASCALE_FLAT_MAX_NUMEL);
+    if (a->grad_dtype != ADASCALE_F32 && a->grad_dtype != ADASCALE_BF16)
+        return fail(nullptr, ADASCALE_EINVAL, "unknown gradient dtype");
+    if (!(a->momentum >= 0.0 && a->momentum < 1.0)) return fail(nullptr, ADASCALE_EINVAL, "momentum outside [0,1)");
+    if (!(a->weight_decay >= 0.0)) return fail(nullptr, ADASCALE_EINVAL, "negative weight decay");
+    if (!(a->theta < 1.0)) return fail(nullptr, ADASCALE_EINVAL, "theta must be < 1");
+    if (!a->lr_table || a->lr_table_len < 1) return fail(nullptr, ADASCALE_EINVAL, "empty lr table");
+    if (a->flags & ~(ADASCALE_LAGGED_R | ADASCALE_EST_NORM_RATIO | ADASCALE_NO_POINTER_CHECK))
+        return fail(nullptr, ADASCALE_EINVAL, "flag not supported by adascale_step_flat");
+    if (!a->state || (uintptr_t)a->state % 8) return fail(nullptr, ADASCALE_EINVAL, "null or misaligned state record");
+    if (a->device < 0 || a->device >= kMaxDevices) return fail(nullptr, ADASCALE_EINVAL, "no such device");
+    const size_t gb = a->grad_dtype == ADASCALE_F32 ? 4 : 2;
+    FlatPointers fp{};
+    if (a->numel > 0) {
+        if (!a->w || !a->mom || !a->grads) return fail(nullptr, ADASCALE_EINVAL, "null tensor pointer");
+        if ((uintptr_t)a->w % 4 || (uintptr_t)a->mom % 4) return fail(nullptr, ADASCALE_EINVAL, "misaligned tensor pointer");
+        fp.w = (unsigned long long)(uintptr_t)a->w;
+        fp.v = (unsigned long long)(uintptr_t)a->mom;
+        for (int i = 0; i < a->S; ++i) {
+            if (!a->grads[i] || (uintptr_t)a->grads[i] % gb)
+                return fail(nullptr, ADASCALE_EINVAL, "null or misaligned gradient pointer (buffer %d)", i);
+            fp.g[i] = (unsigned long long)(uintptr_t)a->grads[i];
+        }
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    DeviceGuard guard;
+    HIP_TRY(nullptr, guard.enter(a->device));
+    if (a->numel > 0 && !(a->flags & ADASCALE_NO_POINTER_CHECK)) {
+        uintptr_t lo = 1, hi = 0;
+        bool ok = device_range_ok(a->w, (size_t)a->numel * 4, a->device, lo, hi) &&
+                  device_range_ok(a->mom, (size_t)a->numel * 4, a->device, lo, hi);
+        for (int i = 0; i < a->S && ok; ++i) ok = device_range_ok(a->grads[i], (size_t)a->numel * gb, a->device, lo, hi);
+        if (!ok) return fail(nullptr, ADASCALE_EINVAL, "a tensor pointer is not device memory of %lld elements", (long long)a->numel);
+    }
+    FlatScratch *sc = nullptr;
+    HIP_TRY(nullptr, flat_scratch_on(a->device, &sc));
+
+    const int vec = a->grad_dtype == ADASCALE_F32 ? 4 : 8;
+    const long long tile = (long long)kThreads * vec;
+    const int n_tiles = (int)((a->numel + tile - 1) / tile);
+    const int grid = std::max(1, std::min(n_tiles, kFlatMaxGrid));
+    const double theta = a->theta < 0.0 ? std::max(1.0 - a->S / 1000.0, 0.0) : a->theta;
+    const ScalarArgs sa{a->S, a->flags, theta, a->eps <= 0.0 ? 1e-6 : a->eps, (long long)a->lr_table_len};
+    const double inv_S = 1.0 / (double)a->S;
+    const float rho = (float)a->momentum, lambda = (float)a->weight_decay;
+    adascale_state *user = static_cast<adascale_state *>(a->state);
+
+    hipLaunchKernelGGL(k_flat_setup, dim3(1), dim3(kFlatMaxScale), 0, s, sc, fp, a->S, user);
+#define LAUNCH(GT, HH) hipLaunchKernelGGL((k_flat_sweep<GT, HH>), dim3(grid), dim3(kThreads), 0, s, sc, (long long)a->numel, n_tiles, a->S, inv_S, rho, lambda)
+    if (a->grad_dtype == ADASCALE_F32) {
+        if (a->S >= 16) LAUNCH(float, 8);
+        else if (a->S >= 4) LAUNCH(float, 2);
+        else LAUNCH(float, 1);
+    } else {
+        if (a->S >= 16) LAUNCH(Bf16, 8);
+        else if (a->S >= 4) LAUNCH(Bf16, 2);
+        else LAUNCH(Bf16, 1);
+    }
+#undef LAUNCH
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, &sc->partials[0][0], grid, &sc->st[0], &sc->st[1],
+                       a->lr_table, sa);
+    if (vec == 4) hipLaunchKernelGGL(k_flat_finish<4>, dim3(grid), dim3(kThreads), 0, s, sc, (long long)a->numel, n_tiles, user);
+    else hipLaunchKernelGGL(k_flat_finish<8>, dim3(grid), dim3(kThreads), 0, s, sc, (long long)a->numel, n_tiles, user);
+    HIP_TRY(nullptr, hipGetLastError());
     return ADASCALE_OK;
 }
 

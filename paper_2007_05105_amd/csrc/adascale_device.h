@@ -1334,6 +1334,119 @@ __global__ void k_set_state(DevState *st, long long step, double tau, double sba
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Step on one flat tensor without a context (adascale_step_flat): every byte of device memory the
+// kernels need beyond the caller's buffers -- the pointer row, two state records, the partial
+// sums -- lies in one fixed block whose address the host passes in.  Three launches plus a set-up
+// kernel: the gradient sweep leaves the new momentum in v (it does not depend on eta_t), k_scalars
+// evaluates the estimator, the last kernel applies w <- w - eta_t v and hands the state back.
+constexpr int kFlatMaxScale = 64;     // gradient pointers travel as a kernel argument
+constexpr int kFlatMaxGrid = 2048;    // workgroups of the sweep = partial slots
+
+struct FlatScratch {
+    unsigned long long row[kRowG + kFlatMaxScale];  // [w, v, unused, g_0 .. g_{S-1}]
+    DevState st[2];                                 // before / after the step
+    alignas(16) double partials[kFlatMaxGrid][2];   // k_scalars reads them as pairs
+};
+
+struct FlatPointers {
+    unsigned long long w, v, g[kFlatMaxScale];
+};
+
+// The block keeps whatever the last call left in it: everything a call reads is written here or
+// by its own sweep first (pointer row, the state record of before the step, and -- by the sweep --
+// exactly the partial slots k_scalars is told to add).
+__global__ void k_flat_setup(FlatScratch *sc, FlatPointers ptrs, int S, const adascale_state *user)
+{
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        sc->row[kRowW] = ptrs.w;
+        sc->row[kRowV] = ptrs.v;
+        sc->row[kRowGbar] = 0;
+        DevState st{};
+        st.step = user->step;
+        st.tau = user->tau;
+        st.sig_bar = user->sigma2_bar;
+        st.mu_bar = user->mu2_bar;
+        sc->st[0] = st;
+    }
+    if (tid < S) sc->row[kRowG + tid] = ptrs.g[tid];
+}
+
+template <typename GT, int HG>
+__global__ __launch_bounds__(kThreads) void k_flat_sweep(FlatScratch *sc, long long numel, int n_tiles, int S,
+                                                         double inv_S, float rho, float lambda)
+{
+    constexpr int VEC = Traits<GT>::VEC;
+    constexpr int TILE = kThreads * VEC;
+    const int tid = threadIdx.x;
+    __shared__ double sh[kWaves][2];
+    const unsigned long long *row = sc->row;
+    double acc_a = 0.0, acc_b = 0.0;
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const long long base = (long long)t * TILE + (long long)tid * VEC;
+        const long long rem = numel - base;
+        if (rem <= 0) continue;
+        const float *w = reinterpret_cast<const float *>(row[kRowW]) + base;
+        float *v = reinterpret_cast<float *>(row[kRowV]) + base;
+        if (rem >= VEC) {
+            float wv[VEC], vv[VEC], gv[VEC];
+            load_f32<VEC>(v, vv);
+            if (lambda != 0.f) load_f32<VEC>(w, wv);
+            reduce_lane_full<GT, HG>(row, base, S, inv_S, gv, acc_a, acc_b);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) vv[e] = fmaf(rho, vv[e], lambda != 0.f ? fmaf(lambda, wv[e], gv[e]) : gv[e]);
+            store_f32<VEC>(v, vv);
+        } else {
+            for (int e = 0; e < (int)rem; ++e) {
+                const float g = reduce_element<GT>(row, base + e, S, inv_S, acc_a, acc_b);
+                v[e] = fmaf(rho, v[e], lambda != 0.f ? fmaf(lambda, w[e], g) : g);
+            }
+        }
+    }
+    reduce_store_partial(acc_a, acc_b, sh, &sc->partials[0][0], blockIdx.x);
+}
+
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void k_flat_finish(const FlatScratch *sc, long long numel, int n_tiles,
+                                                          adascale_state *user)
+{
+    constexpr int TILE = kThreads * VEC;
+    const int tid = threadIdx.x;
+    const DevState &st = sc->st[1];
+    const float eta = st.eta_f32;
+    float *wp = reinterpret_cast<float *>(sc->row[kRowW]);
+    const float *vp = reinterpret_cast<const float *>(sc->row[kRowV]);
+    for (int t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const long long base = (long long)t * TILE + (long long)tid * VEC;
+        const long long rem = numel - base;
+        if (rem <= 0) continue;
+        if (rem >= VEC) {
+            float wv[VEC], vv[VEC];
+            load_f32<VEC>(wp + base, wv);
+            load_f32<VEC>(vp + base, vv);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) wv[e] = fmaf(-eta, vv[e], wv[e]);
+            store_f32<VEC>(wp + base, wv);
+        } else {
+            for (int e = 0; e < (int)rem; ++e) wp[base + e] = fmaf(-eta, vp[base + e], wp[base + e]);
+        }
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        user->step = st.step;
+        user->tau = st.tau;
+        user->r = st.r;
+        user->lr_eff = st.lr_eff;
+        user->sum_sq = st.A;
+        user->sq_mean = st.B;
+        user->sigma2_hat = st.sig_hat;
+        user->mu2_hat = st.mu_hat;
+        user->sigma2_bar = st.sig_bar;
+        user->mu2_bar = st.mu_bar;
+        user->done = st.done;
+    }
+}
+
 // Register-slot counts the fused kernel is instantiated for (the host uses the largest one that
 // every workgroup can fill).
 constexpr int kFRegLevels = 4;

@@ -48,12 +48,15 @@ def test_struct_layouts_match_header(tmp_path):
     fields_s = [n for n, _ in binding.State._fields_]
     fields_p = [n for n, _ in binding.PlanInfo._fields_]
     fields_t = [n for n, _ in binding.Tuning._fields_]
+    fields_f = [n for n, _ in binding.FlatStep._fields_]
     body = "".join(f'printf("%zu\\n", offsetof(adascale_config, {f}));' for f in fields_c)
     body += "".join(f'printf("%zu\\n", offsetof(adascale_state, {f}));' for f in fields_s)
     body += "".join(f'printf("%zu\\n", offsetof(adascale_plan_info, {f}));' for f in fields_p)
     body += 'printf("%zu\\n", sizeof(adascale_plan_info));'
     body += "".join(f'printf("%zu\\n", offsetof(adascale_tuning, {f}));' for f in fields_t)
     body += 'printf("%zu\\n", sizeof(adascale_tuning));'
+    body += "".join(f'printf("%zu\\n", offsetof(adascale_flat_step, {f}));' for f in fields_f)
+    body += 'printf("%zu\\n%d\\n%lld\\n", sizeof(adascale_flat_step), ADASCALE_FLAT_MAX_SCALE, (long long)ADASCALE_FLAT_MAX_NUMEL);'
     src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "adascale_diag.h"\nint main(void){'
                    'printf("%zu\\n%zu\\n", sizeof(adascale_config), sizeof(adascale_state));' + body + "return 0;}")
     exe = tmp_path / "layout"
@@ -63,6 +66,8 @@ def test_struct_layouts_match_header(tmp_path):
     got = [getattr(binding.Config, f).offset for f in fields_c] + [getattr(binding.State, f).offset for f in fields_s]
     got += [getattr(binding.PlanInfo, f).offset for f in fields_p] + [C.sizeof(binding.PlanInfo)]
     got += [getattr(binding.Tuning, f).offset for f in fields_t] + [C.sizeof(binding.Tuning)]
+    got += [getattr(binding.FlatStep, f).offset for f in fields_f] + [C.sizeof(binding.FlatStep)]
+    got += [binding.FLAT_MAX_SCALE, binding.FLAT_MAX_NUMEL]
     assert out[2:] == got
 
 
