@@ -108,3 +108,53 @@ def test_linear_scaling_baseline_runs_through_a_scale_one_context():
     _, loss_as, _, _, _ = train(S, with_oracle=False)
     print("S = 16: LSW objective", loss_lsw, "after", steps, "iterations; AdaScale", loss_as, flush=True)
     assert math.isfinite(loss_lsw)
+
+
+def test_noisy_quadratic_sits_under_the_bound_of_theorem_2():
+    """Theorem 2 (Sec. 3.3): for an alpha-PL, beta-smooth objective with gradient variance at most
+    V, constant lr(t) = eta < 2/beta and S <= 1/gamma, AdaScale SGD (no momentum) ends with
+        E[F(w_T) - F*] <= (1 - gamma)^(rbar T) [F(w_0) - F*] + Delta,
+        gamma = eta alpha (2 - eta beta),  Delta = eta^2 beta V / (2 gamma),
+    where rbar T = tau_T: the same bound, with the same constants, at every scale.  Here
+    F(w) = 1/2 sum_j h_j (w_j - c_j)^2 with h_j in [0.5, 2] (alpha = 0.5, beta = 2), per-batch
+    gradients = the exact gradient + N(0, 1) noise per coordinate (V = d), F* = 0.  F is a sum over
+    20000 independent coordinates, so one run sits within about a percent of its expectation.  The
+    run stops when tau >= T_SI, so the bound is evaluated at the tau the run ended with; it is
+    checked at two budgets: the first term shrinks with T_SI, the floor Delta does not depend on S."""
+    h, c, _ = problem()
+    alpha, beta, eta, V = 0.5, 2.0, 0.05, float(D)
+    assert float(h.min()) >= alpha and float(h.max()) <= beta
+    gamma = eta * alpha * (2.0 - eta * beta)
+    delta = eta ** 2 * beta * V / (2.0 * gamma)
+    f0 = float(0.5 * torch.sum(h * c ** 2))
+    seen = {}
+    for budget in (100, 400):
+        for S in (1, 4, 16):
+            assert S <= 1.0 / gamma                                     # the theorem's condition on the scale
+            w, v = [torch.zeros(D, device="cuda:0")], [torch.zeros(D, device="cuda:0")]
+            gen = torch.Generator(device="cuda:0")
+            gen.manual_seed(1000 * budget + S)
+            ada = AdaScale([D], S, np.full(budget, eta, dtype=np.float32), momentum=0.0)
+            grads = [[torch.empty(D, device="cuda:0")] for _ in range(S)]
+
+            def make_grads(t):
+                base = h * (w[0] - c)
+                for i in range(S):
+                    grads[i][0].copy_(base + torch.randn(D, generator=gen, device="cuda:0"))
+                return grads
+
+            steps = run_until_done(ada, w, v, make_grads, max_steps=budget)
+            st = ada.get_state()
+            ada.close()
+            f = float(0.5 * torch.sum(h * (w[0] - c) ** 2))
+            bound = (1.0 - gamma) ** st.tau * f0 + delta
+            seen[(budget, S)] = (steps, st.tau, f, bound)
+            print(f"T_SI {budget} S {S}: {steps} iterations, tau {st.tau:.1f}, F - F* = {f:.1f}, bound {bound:.1f} "
+                  f"(floor {delta:.1f}, start {f0:.1f})", flush=True)
+            assert st.done and math.ceil(budget / S) <= steps <= budget
+            assert f <= bound
+    # the bound says something: its floor is a small part of the initial gap, and at the larger
+    # budget the first term has gone, so every scale sits under the same number
+    assert delta < 0.1 * f0
+    assert max(seen[(400, S)][3] for S in (1, 4, 16)) <= 1.0001 * delta
+    assert seen[(400, 16)][0] < seen[(400, 4)][0] < seen[(400, 1)][0] == 400
