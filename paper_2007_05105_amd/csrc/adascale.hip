@@ -90,6 +90,7 @@ struct adascale_ctx {
     size_t tab_len[kTables] = {};      // 0: table j holds nothing
     unsigned long long tab_used[kTables] = {};  // step count of the last use (the oldest is replaced)
     unsigned long long steps_issued = 0;
+    int tab_last = 0;                  // table of the last step
     std::vector<unsigned long long> tab_build;  // the table of the current call
     float *d_gbar = nullptr, *d_lr = nullptr;
     double *d_partials = nullptr;
@@ -795,8 +796,10 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
                 row[kRowG + i] = (unsigned long long)(uintptr_t)grads[(size_t)std::min(i, S - 1) * N + k];
         }
         int slot = -1;
-        for (int j = 0; j < kTables && slot < 0; ++j)
+        for (int i = 0; i < kTables && slot < 0; ++i) {  // the table of the last step first
+            const int j = (c->tab_last + i) % kTables;
             if (c->tab_len[j] == len && memcmp(c->h_tab[j], tab, len * sizeof(unsigned long long)) == 0) slot = j;
+        }
         if (slot < 0) {
             const size_t gb = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
             uintptr_t lo = 1, hi = 0;
@@ -828,6 +831,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             c->tab_len[slot] = len;
         }
         c->tab_used[slot] = c->steps_issued;
+        c->tab_last = slot;
         d_ptrs = c->d_tab[slot];
     }
 

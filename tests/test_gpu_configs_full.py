@@ -15,9 +15,10 @@ import workloads as W
 pytestmark = pytest.mark.gpu
 
 # Free-running: fp32 storage of w and v on the GPU against the fp64 oracle.  Each step adds a
-# rounding of relative size 2^-24 to w and v; over T steps the momentum filter (gain 1/(1-rho))
-# lets the difference grow to a few T * 2^-24 / (1-rho) of max|w| at worst.
-DRIFT_TOL = {1: 1e-5, 2: 2e-4, 3: 1e-4, 4: 1e-3}
+# rounding of relative size 2^-24 to w and v; the roundings are independent, so over T steps the
+# difference grows like sqrt(T) of that, stretched by the momentum filter's gain 1/(1-rho).
+# Observed: 1.8e-7 (cfg1), 1.1e-6 (cfg2, 200 steps), 8.3e-7 (cfg3), 6.8e-7 (cfg4) of max|w|.
+DRIFT_TOL = 1e-5
 
 
 def log(msg):
@@ -41,7 +42,7 @@ def full_run(cfg, every):
     log(f"cfg{cfg}: free-running oracle after {rep.free['steps']} steps: drift of w {rep.free['w_drift']:.3g} of max|w|, "
         f"r {rep.free['rel']['r']:.3g}, tau {rep.free['rel']['tau']:.3g}")
     assert max(rep.free["rel"][k] for k in ("r", "tau", "sigma2_bar", "mu2_bar")) <= H.TOL_SCALAR
-    assert rep.free["w_drift"] <= DRIFT_TOL[cfg]
+    assert rep.free["w_drift"] <= DRIFT_TOL
     return rep
 
 

@@ -158,3 +158,31 @@ def test_noisy_quadratic_sits_under_the_bound_of_theorem_2():
     assert delta < 0.1 * f0
     assert max(seen[(400, S)][3] for S in (1, 4, 16)) <= 1.0001 * delta
     assert seen[(400, 16)][0] < seen[(400, 4)][0] < seen[(400, 1)][0] == 400
+
+
+def test_run_log_has_one_record_per_poll(tmp_path):
+    """The per-step log of the driver loop: iteration, gain, learning rate, clock, estimates."""
+    import json
+    S, budget = 4, 40
+    h, c, _ = problem()
+    w, v = [torch.zeros(D, device="cuda:0")], [torch.zeros(D, device="cuda:0")]
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(5)
+    ada = AdaScale([D], S, np.full(budget, 0.05, dtype=np.float32))
+    grads = [[torch.empty(D, device="cuda:0")] for _ in range(S)]
+
+    def make_grads(t):
+        base = h * (w[0] - c)
+        for i in range(S):
+            grads[i][0].copy_(base + torch.randn(D, generator=gen, device="cuda:0"))
+        return grads
+
+    path = tmp_path / "run.jsonl"
+    steps = run_until_done(ada, w, v, make_grads, max_steps=budget, log_path=str(path))
+    final = ada.get_state()
+    ada.close()
+    rows = [json.loads(l) for l in open(path)]
+    assert [r["iteration"] for r in rows] == list(range(1, steps + 1))
+    assert all(1.0 <= r["r"] <= S and r["step"] == r["iteration"] for r in rows)
+    assert all(b["tau"] == a["tau"] + b["r"] for a, b in zip(rows, rows[1:]))      # tau_{t+1} = tau_t + r_t
+    assert rows[-1]["done"] == 1 and rows[-1]["tau"] == final.tau and all(r["done"] == 0 for r in rows[:-1])
