@@ -310,11 +310,34 @@ __device__ __forceinline__ double gain_from(const ScalarArgs &c, double sbar, do
     return den > 0.0 ? (sbar + mbar) / den : 1.0;
 }
 
-// The estimator and the clock, evaluated by one lane.  Reads the state of before the step from
-// `in`, writes the state of after the step to `out` (two different records: other workgroups may
-// still be reading `in`).  Returns eta_t.
-__device__ __forceinline__ float eval_scalars(double A, double B, const DevState *__restrict__ in,
-                                              DevState *__restrict__ out, const float *__restrict__ lr,
+// What the scalar evaluation needs of the state before the step, and the learning rate of the
+// step: lr(floor(tau_t)), with tau_t of BEFORE the step (Sec. 3.2) -- none of it depends on this
+// step's gradients, so it can be fetched while they are still being summed.
+struct ScalarIn {
+    long long step;
+    double tau, sig_bar, mu_bar;
+    float lr_now;
+};
+
+__device__ __forceinline__ ScalarIn load_scalar_in(const DevState *__restrict__ in, const float *__restrict__ lr,
+                                                   const ScalarArgs &c)
+{
+    ScalarIn s;
+    s.step = in->step;
+    s.tau = in->tau;
+    s.sig_bar = in->sig_bar;
+    s.mu_bar = in->mu_bar;
+    long long idx = (long long)floor(s.tau);
+    if (idx > c.L - 1) idx = c.L - 1;
+    if (idx < 0) idx = 0;
+    s.lr_now = lr[idx];
+    return s;
+}
+
+// The estimator and the clock, evaluated by one lane from the sums A, B and the state of before
+// the step; writes the state of after the step to `out` (another record than the one `in` was
+// read from: other workgroups may still be reading that).  Returns eta_t.
+__device__ __forceinline__ float eval_scalars(double A, double B, const ScalarIn &in, DevState *__restrict__ out,
                                               const ScalarArgs &c, bool write)
 {
     const int S = c.S;
@@ -334,21 +357,18 @@ __device__ __forceinline__ float eval_scalars(double A, double B, const DevState
         x1 = S >= 2 ? fmax(sig, c.eps) : 0.0;
         x2 = fmax(mu, 0.0);
     }
-    const long long step = in->step;
+    const long long step = in.step;
     const long long k = step + 1;
     const double alpha = fmax(1.0 - c.theta, 1.0 / (double)k);
-    double sbar = in->sig_bar, mbar = in->mu_bar;
+    double sbar = in.sig_bar, mbar = in.mu_bar;
     double r = 1.0;
     if (c.flags & ADASCALE_LAGGED_R) r = step == 0 ? 1.0 : gain_from(c, sbar, mbar);
     sbar += alpha * (x1 - sbar);
     mbar += alpha * (x2 - mbar);
     if (!(c.flags & ADASCALE_LAGGED_R)) r = gain_from(c, sbar, mbar);
 
-    const double tau = in->tau;
-    long long idx = (long long)floor(tau);
-    if (idx > c.L - 1) idx = c.L - 1;
-    if (idx < 0) idx = 0;
-    const double eta = r * (double)lr[idx];
+    const double tau = in.tau;
+    const double eta = r * (double)in.lr_now;
     if (write) {
         out->A = A;
         out->B = B;
@@ -375,6 +395,8 @@ __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__rest
 {
     __shared__ double sh_a[kScalarThreads], sh_b[kScalarThreads];
     const int tid = threadIdx.x;
+    ScalarIn sin{};
+    if (tid == 0) sin = load_scalar_in(st_in, lr, c);  // in flight while the partials are summed
     typedef double d2 __attribute__((ext_vector_type(2)));
     const d2 *p2 = reinterpret_cast<const d2 *>(partials);
     double a = 0.0, b = 0.0;
@@ -402,7 +424,7 @@ __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__rest
         }
         __syncthreads();
     }
-    if (tid == 0) eval_scalars(sh_a[0], sh_b[0], st_in, st_out, lr, c, true);
+    if (tid == 0) eval_scalars(sh_a[0], sh_b[0], sin, st_out, c, true);
 }
 
 // eta_t of the prior-iteration variant (App. B.3): r_t from the averages as they stand before
@@ -1082,6 +1104,10 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         // side, and the arrival count is bumped only after this workgroup's stores have completed.
         // That avoids a whole-L2 write-back and invalidate at the barrier; nothing else written in
         // phase 1 (scratch tiles) is read by another workgroup.
+        // (the state of before the step and lr(floor(tau_t)) do not depend on the sums: lane 0
+        // fetches them here, behind the wait for the partial store and for the other workgroups)
+        ScalarIn sin{};
+        if (tid == 0) sin = load_scalar_in(p.st_in, p.lr, p.sc);
         if (tid < 2) {
             double t = red[0][tid];
     #pragma unroll
@@ -1132,7 +1158,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
             }
             __syncthreads();
         }
-        if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], p.st_in, p.st_out, p.lr, p.sc, b == 0);
+        if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], sin, p.st_out, p.sc, b == 0);
         __syncthreads();
         eta = sh_eta;
     }
