@@ -966,18 +966,15 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     hipLaunchKernelGGL((k_update<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
                        c->d_numel, d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,     \
                        lambda)
-#define LAUNCH_APPLY(VV)                                                                                    \
-    hipLaunchKernelGGL((k_apply<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix,  \
-                       c->d_numel, d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len)
         if (stream_fn && c->stream_momentum) {
-            if (c->vec == 4) LAUNCH_APPLY(4);
-            else LAUNCH_APPLY(8);
+            ApplyArgs aa{c->d_ftiles, c->d_ctiles, c->d_numel, d_ptrs, st_out, (int)c->ftiles.size(), (int)c->ctiles.size(),
+                         row_len};
+            hipLaunchKernelGGL(k_apply, dim3(c->s_grid), dim3(kFThreads), 0, s, aa);
         } else {
             if (c->vec == 4) LAUNCH(4);
             else LAUNCH(8);
         }
 #undef LAUNCH
-#undef LAUNCH_APPLY
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[3], s));

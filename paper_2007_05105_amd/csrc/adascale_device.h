@@ -440,49 +440,6 @@ __device__ __forceinline__ float lagged_eta(const DevState *__restrict__ st, con
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply: w <- w - eta_t v, for the steps whose gradient sweep has already left the new
-// momentum in v (12 bytes per parameter instead of the 20 of k_update).  Plain loads and stores:
-// at d = 351 M streaming stores change nothing here (8.44 ms per step either way) and streaming
-// loads cost 7 % of this kernel's time.
-template <int VEC>
-__global__ __launch_bounds__(kThreads) void k_apply(const int *__restrict__ span_first,
-                                                    const int *__restrict__ tile_prefix,
-                                                    const long long *__restrict__ numel,
-                                                    const unsigned long long *__restrict__ ptrs,
-                                                    const DevState *__restrict__ st, int n_tiles, int span_tiles,
-                                                    int n_spans, int row_len)
-{
-    constexpr int TILE = kThreads * VEC;
-    const int tid = threadIdx.x;
-    const float eta = st->eta_f32;
-
-    for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
-        const int t0 = span * span_tiles;
-        const int t1 = min(t0 + span_tiles, n_tiles);
-        int k = span_first[span];
-        for (int t = t0; t < t1; ++t) {
-            while (t >= tile_prefix[k + 1]) ++k;
-            const long long base = (long long)(t - tile_prefix[k]) * TILE + (long long)tid * VEC;
-            const long long rem = numel[k] - base;
-            if (rem <= 0) continue;
-            const unsigned long long *row = ptrs + (size_t)k * row_len;
-            float *w = reinterpret_cast<float *>(row[kRowW]) + base;
-            const float *v = reinterpret_cast<const float *>(row[kRowV]) + base;
-            if (rem >= VEC) {
-                float wv[VEC], vv[VEC];
-                load_f32<VEC>(w, wv);
-                load_f32<VEC>(v, vv);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) wv[e] = fmaf(-eta, vv[e], wv[e]);
-                store_f32<VEC>(w, wv);
-            } else {
-                for (int e = 0; e < (int)rem; ++e) w[e] = fmaf(-eta, v[e], w[e]);
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
 // single pass (prior-iteration gain): reduce and update in one sweep, S*d*b + 16*d bytes.  The
 // mean gradient never goes to memory; k_scalars afterwards folds A and B into the averages.
 template <typename GT, int HG>
@@ -1368,6 +1325,71 @@ __global__ void k_set_state(DevState *st, long long step, double tau, double sba
         st->sig_bar = sbar;
         st->mu_bar = mbar;
         st->done = tau >= (double)L;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// apply: w <- w - eta_t v, the last kernel of the three-kernel step whose gradient sweep has left
+// the new momentum in v (12 bytes per parameter instead of the 20 of k_update).  Persistent
+// workgroups, one per compute unit, walk the full tiles in memory order, two tiles a stride of
+// the grid apart per round with all four loads ahead of the two stores (the chip then works on a
+// front 2 x 256 tiles wide).  Measured against one workgroup per span of two 256-lane tiles in
+// dispatch order, at d = 351 M: 705 against 757 us; one tile per round 776, three 772, four 796,
+// two adjacent tiles 772, two workgroups per compute unit 860; streaming stores change nothing
+// and streaming loads cost 4-15 %, so the accesses are plain ones.
+struct ApplyArgs {
+    const FTile *tiles, *cold;     // full and ragged tiles, read through the constant address space
+    const long long *numel;
+    const unsigned long long *ptrs;
+    const DevState *st;
+    int n_tiles, n_cold, row_len;
+};
+
+constexpr int kApplyRound = 2;  // tiles per workgroup and round
+
+__global__ __launch_bounds__(kFThreads) void k_apply(ApplyArgs p)
+{
+    constexpr int U = kApplyRound;
+    const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
+    const unsigned lane_off = (unsigned)tid * 16u;
+    const float eta = p.st->eta_f32;
+    auto locate = [&](int t) -> FLoc {
+        const AS_CONST int *tp = (const AS_CONST int *)p.tiles + 2 * (size_t)t;
+        return FLoc{(cp_u64)p.ptrs + (size_t)tp[0] * p.row_len, (unsigned long long)tp[1] * (kFTile * 4ULL)};
+    };
+    int t = b;
+    for (; t + (U - 1) * G < p.n_tiles; t += U * G) {
+        gp_char w[U];
+        f4 wv[U], vv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const FLoc L = locate(t + u * G);
+            w[u] = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
+            wv[u] = *(gp_cf4)w[u];
+            vv[u] = *(gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            *(gp_f4)w[u] = f4{fmaf(-eta, vv[u].x, wv[u].x), fmaf(-eta, vv[u].y, wv[u].y), fmaf(-eta, vv[u].z, wv[u].z),
+                              fmaf(-eta, vv[u].w, wv[u].w)};
+    }
+    for (; t < p.n_tiles; t += G) {  // the last, incomplete round
+        const FLoc L = locate(t);
+        gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
+        const f4 wv = *(gp_cf4)w, vv = *(gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off);
+        *(gp_f4)w = f4{fmaf(-eta, vv.x, wv.x), fmaf(-eta, vv.y, wv.y), fmaf(-eta, vv.z, wv.z), fmaf(-eta, vv.w, wv.w)};
+    }
+    for (int c = b; c < p.n_cold; c += G) {  // ragged last tiles of the tensors
+        const AS_CONST int *tp = (const AS_CONST int *)p.cold + 2 * (size_t)c;
+        const int k = tp[0], local = tp[1];
+        cp_u64 row = (cp_u64)p.ptrs + (size_t)k * p.row_len;
+        const long long first = (long long)local * kFTile + (long long)tid * 4;
+        const long long rem = ((const AS_CONST long long *)p.numel)[k] - first;
+        if (rem <= 0) continue;
+        AS_GLOBAL float *w = (AS_GLOBAL float *)row[kRowW] + first;
+        const AS_GLOBAL float *v = (const AS_GLOBAL float *)row[kRowV] + first;
+        const int n = rem < 4 ? (int)rem : 4;
+        for (int e = 0; e < n; ++e) w[e] = fmaf(-eta, v[e], w[e]);
     }
 }
 
