@@ -128,6 +128,18 @@ int adascale_init(const adascale_config *cfg, adascale_ctx **out);
  * A tensor with numel 0 may have
  * null pointers.  EINVAL on a null required pointer, or (unless NO_POINTER_CHECK) a pointer
  * that is not device memory of sufficient extent; nothing is launched in that case.
+ *
+ * HIP graphs.  A step may be captured (hip_stream in capture mode) and the graph replayed: all
+ * that changes from step to step -- which state record is current, the generation of the fused
+ * step's grid barrier, the work counters -- is kept on the device and advanced by the kernels, so
+ * every replay is one more iteration on whatever the gradient buffers hold at that moment.
+ * Conditions: the same tensor pointers must have been through one adascale_step outside the
+ * capture (their table is then on the device; during capture nothing is uploaded, checked or
+ * allocated, and ADASCALE_ESTATE says so otherwise); not with ADASCALE_COOPERATIVE_LAUNCH; the
+ * graph is void after adascale_set_scale or adascale_destroy; replays, like direct calls, must
+ * not overlap other steps of the same context, and keeping a replayed fused step apart from
+ * fused steps running on other streams is the caller's business (direct calls are chained by the
+ * library).  adascale_set_state may be captured too; adascale_get_state may not (it waits).
  */
 int adascale_step(adascale_ctx *ctx, void *const *w, void *const *mom, const void *const *grads,
                   void *hip_stream);

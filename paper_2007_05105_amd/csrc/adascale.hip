@@ -91,29 +91,27 @@ struct adascale_ctx {
     unsigned long long tab_used[kTables] = {};  // step count of the last use (the oldest is replaced)
     unsigned long long steps_issued = 0;
     int tab_last = 0;                  // table of the last step
+    bool tab_captured[kTables] = {};   // a captured step refers to table j: it is never replaced
     std::vector<unsigned long long> tab_build;  // the table of the current call
     float *d_gbar = nullptr, *d_lr = nullptr;
     double *d_partials = nullptr;
-    DevState *d_state = nullptr;     // two records: [cur] is current, a step writes [cur ^ 1]
-    int cur = 0;
-    int *d_fault = nullptr;
+    // Progress of the context (current state record, barrier generation, fault flag, claim
+    // counter): kept on the device and advanced by the kernels, so that the host passes the same
+    // arguments at every step and a captured step can be replayed.
+    DevBook *d_book = nullptr;
 
     // fused single-launch path
     std::vector<FTile> ftiles, ctiles;   // full tiles, ragged last tiles
     FTile *d_ftiles = nullptr, *d_ctiles = nullptr;
-    unsigned long long *d_barrier = nullptr;
-    unsigned long long fused_launches = 0;
     int f_grid = 0, f_tpb = 0, f_lds_cap = 0, f_level = 0;
     bool fused_ok = false;
 
     // streaming reduce (first kernel of the three-kernel step)
     bool tiles_ok = false, stream_ok = false;
     int n_cus = 0, s_grid = 0;
-    unsigned *d_claim = nullptr;         // two counters: a launch uses one and zeroes the other
     bool stream_momentum = true;         // the sweep writes the new momentum instead of the mean gradient
-    unsigned long long stream_launches = 0;
 
-    DevState *h_state = nullptr;    // pinned
+    DevBook *h_book = nullptr;      // pinned
 
     std::vector<hipEvent_t> prof_ev;  // 4 per recorded step
     int prof_cap = 0, prof_n = 0;
@@ -168,7 +166,10 @@ size_t table_len(const adascale_ctx *c, int S)
 
 void forget_tables(adascale_ctx *c)
 {
-    for (int j = 0; j < kTables; ++j) c->tab_len[j] = 0;
+    for (int j = 0; j < kTables; ++j) {
+        c->tab_len[j] = 0;
+        c->tab_captured[j] = false;  // graphs captured before this point are void (see adascale_step)
+    }
 }
 
 int alloc_pointer_tables(adascale_ctx *c, int S)
@@ -371,8 +372,6 @@ int setup_tiles(adascale_ctx *c)
         const void *fn = stream_kernel_for(c->cfg.grad_dtype, S);
         if (fn) HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsPad));
     }
-    HIP_TRY(c, hipMalloc(&c->d_claim, 2 * sizeof(unsigned)));
-    HIP_TRY(c, hipMemset(c->d_claim, 0, 2 * sizeof(unsigned)));
     c->stream_momentum = c->tun.stream_via_scratch != 1;
     c->stream_ok = true;
     return ADASCALE_OK;
@@ -428,14 +427,14 @@ void launch_reduce(const adascale_ctx *c, const unsigned long long *d_ptrs, int 
 
 template <typename GT>
 void launch_reduce_update(const adascale_ctx *c, const unsigned long long *d_ptrs, int grid, hipStream_t s, int S,
-                          const DevState *st, const ScalarArgs &sa)
+                          const ScalarArgs &sa)
 {
     const double inv_S = 1.0 / (double)S;
     const int row_len = padded_scale(c->cfg.grad_dtype, S) + kRowG;
     const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
 #define LAUNCH(HH)                                                                                         \
     hipLaunchKernelGGL((k_reduce_update<GT, HH>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first,       \
-                       c->d_tile_prefix, c->d_numel, d_ptrs, c->d_partials, st, c->d_lr, sa, c->n_tiles,    \
+                       c->d_tile_prefix, c->d_numel, d_ptrs, c->d_partials, c->d_book, c->d_lr, sa, c->n_tiles, \
                        c->span_tiles, c->n_spans, S, row_len, inv_S, rho, lambda)
     if (S >= 16) LAUNCH(8);
     else if (S >= 8) LAUNCH(4);
@@ -636,12 +635,9 @@ int adascale_init_tuned(const adascale_config *cfg, const adascale_tuning *tunin
         // plus one per pair of 512-lane tiles (streaming reduce kernel)
         const size_t n_slots = std::max<size_t>((size_t)c->n_spans, (size_t)kFMaxGrid + (size_t)(c->d / (2 * kFTile)) + 1);
         HIP_TRY(c, hipMalloc(&c->d_partials, sizeof(double) * 2 * n_slots));
-        HIP_TRY(c, hipMalloc(&c->d_state, 2 * sizeof(DevState)));
-        HIP_TRY(c, hipMalloc(&c->d_fault, sizeof(int)));
-        HIP_TRY(c, hipMalloc(&c->d_barrier, sizeof(unsigned long long)));
-        HIP_TRY(c, hipMemset(c->d_fault, 0, sizeof(int)));
-        HIP_TRY(c, hipMemset(c->d_barrier, 0, sizeof(unsigned long long)));
-        HIP_TRY(c, hipHostMalloc(&c->h_state, sizeof(DevState) + sizeof(int), hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc(&c->d_book, sizeof(DevBook)));
+        HIP_TRY(c, hipMemset(c->d_book, 0, sizeof(DevBook)));
+        HIP_TRY(c, hipHostMalloc(&c->h_book, sizeof(DevBook), hipHostMallocDefault));
         for (int j = 0; j < kTables; ++j) HIP_TRY(c, hipEventCreateWithFlags(&c->tab_ev[j], hipEventDisableTiming));
         HIP_TRY(c, hipMemcpy(c->d_span_first, c->span_first.data(), sizeof(int) * c->span_first.size(),
                              hipMemcpyHostToDevice));
@@ -649,7 +645,6 @@ int adascale_init_tuned(const adascale_config *cfg, const adascale_tuning *tunin
         if (N > 0)
             HIP_TRY(c, hipMemcpy(c->d_numel, c->numel.data(), sizeof(long long) * N, hipMemcpyHostToDevice));
         HIP_TRY(c, hipMemcpy(c->d_lr, cfg->lr_table, sizeof(float) * cfg->lr_table_len, hipMemcpyHostToDevice));
-        HIP_TRY(c, hipMemset(c->d_state, 0, 2 * sizeof(DevState)));
         HIP_TRY(c, hipMemset(c->d_partials, 0, sizeof(double) * 2 * n_slots));
         const int trc = setup_tiles(c);
         if (trc != ADASCALE_OK) return trc;
@@ -680,13 +675,10 @@ void adascale_destroy(adascale_ctx *c)
     (void)hipFree(c->d_cold_gbar);
     (void)hipFree(c->d_lr);
     (void)hipFree(c->d_partials);
-    (void)hipFree(c->d_state);
-    (void)hipFree(c->d_fault);
-    (void)hipFree(c->d_barrier);
+    (void)hipFree(c->d_book);
     (void)hipFree(c->d_ftiles);
     (void)hipFree(c->d_ctiles);
-    (void)hipFree(c->d_claim);
-    if (c->h_state) (void)hipHostFree(c->h_state);
+    if (c->h_book) (void)hipHostFree(c->h_book);
     for (int j = 0; j < kTables; ++j) {
         (void)hipFree(c->d_tab[j]);
         if (c->h_tab[j]) (void)hipHostFree(c->h_tab[j]);
@@ -718,8 +710,8 @@ int adascale_set_state(adascale_ctx *c, int64_t step, double tau, double sigma2_
         return fail(c, ADASCALE_EINVAL, "state values must be non-negative");
     DeviceGuard guard;
     HIP_TRY(c, guard.enter(c->cfg.device));
-    hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_state + c->cur, (long long)step,
-                       tau, sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len, c->d_fault);
+    hipLaunchKernelGGL(k_set_state, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, c->d_book, (long long)step, tau,
+                       sigma2_bar, mu2_bar, (long long)c->cfg.lr_table_len);
     HIP_TRY(c, hipGetLastError());
     c->failed = false;
     return ADASCALE_OK;
@@ -732,16 +724,14 @@ int adascale_get_state(adascale_ctx *c, adascale_state *out, void *hip_stream)
     hipStream_t s = (hipStream_t)hip_stream;
     DeviceGuard guard;
     HIP_TRY(c, guard.enter(c->cfg.device));
-    int *h_fault = reinterpret_cast<int *>(c->h_state + 1);
-    HIP_TRY(c, hipMemcpyAsync(c->h_state, c->d_state + c->cur, sizeof(DevState), hipMemcpyDeviceToHost, s));
-    HIP_TRY(c, hipMemcpyAsync(h_fault, c->d_fault, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipMemcpyAsync(c->h_book, c->d_book, sizeof(DevBook), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
-    if (*h_fault) {
+    if (c->h_book->fault) {
         c->failed = true;
         return fail(c, ADASCALE_ESTATE, "a fused step gave up waiting at its grid barrier: w, v and the state are invalid; "
                                         "restore them and call adascale_set_state");
     }
-    const DevState &h = *c->h_state;
+    const DevState &h = c->h_book->st[c->h_book->epoch & 1];
     out->step = h.step;
     out->tau = h.tau;
     out->r = h.r;
@@ -768,10 +758,20 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
 
     if (c->failed)
         return fail(c, ADASCALE_ESTATE, "an earlier step failed at its grid barrier; restore w, v and call adascale_set_state");
+    // Is the stream being captured into a graph?  Then nothing here may wait, copy or allocate, and
+    // what is launched must stay valid for every replay.
+    hipStreamCaptureStatus cap_status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap_status) != hipSuccess) {
+        (void)hipGetLastError();
+        cap_status = hipStreamCaptureStatusNone;
+    }
+    const bool capturing = cap_status != hipStreamCaptureStatusNone;
 
     // the general kernels pass the whole mean gradient through memory
     const int path = adascale_step_path(c);
     if (!c->d_gbar && (path == ADASCALE_PATH_GENERAL || (path == ADASCALE_PATH_STREAMING && !c->stream_momentum))) {
+        if (capturing)
+            return fail(c, ADASCALE_ESTATE, "the first step on the general kernels allocates: run one step outside the capture first");
         HIP_TRY(c, hipMalloc(&c->d_gbar, sizeof(float) * c->gbar_len));
         forget_tables(c);  // they point at the ragged-tile scratch
     }
@@ -800,6 +800,9 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             const int j = (c->tab_last + i) % kTables;
             if (c->tab_len[j] == len && memcmp(c->h_tab[j], tab, len * sizeof(unsigned long long)) == 0) slot = j;
         }
+        if (slot < 0 && capturing)
+            return fail(c, ADASCALE_ESTATE, "this set of tensor pointers has no table on the device yet: run one step with it "
+                                            "outside the capture first");
         if (slot < 0) {
             const size_t gb = c->cfg.grad_dtype == ADASCALE_F32 ? 4 : 2;
             uintptr_t lo = 1, hi = 0;
@@ -817,9 +820,12 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
                                     c->numel[k]);
                 }
             }
-            slot = 0;  // an empty table if there is one, else the one used longest ago
-            for (int j = 1; j < kTables && c->tab_len[slot] != 0; ++j)
-                if (c->tab_len[j] == 0 || c->tab_used[j] < c->tab_used[slot]) slot = j;
+            slot = -1;  // an empty table if there is one, else the one used longest ago; never one a graph refers to
+            for (int j = 0; j < kTables && (slot < 0 || c->tab_len[slot] != 0); ++j) {
+                if (c->tab_captured[j]) continue;
+                if (slot < 0 || c->tab_len[j] == 0 || c->tab_used[j] < c->tab_used[slot]) slot = j;
+            }
+            if (slot < 0) return fail(c, ADASCALE_ESTATE, "every pointer table of this context is held by a captured step");
             // the mirror is the staging buffer: its last upload must have left it (long ago, normally)
             if (c->tab_uploaded[slot]) HIP_TRY(c, hipEventSynchronize(c->tab_ev[slot]));
             c->tab_len[slot] = 0;
@@ -832,15 +838,14 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         }
         c->tab_used[slot] = c->steps_issued;
         c->tab_last = slot;
+        if (capturing) c->tab_captured[slot] = true;
         d_ptrs = c->d_tab[slot];
     }
 
     hipEvent_t *pe = nullptr;
-    if (c->prof_on && c->prof_n < c->prof_cap) pe = &c->prof_ev[(size_t)4 * c->prof_n++];
+    if (c->prof_on && c->prof_n < c->prof_cap && !capturing) pe = &c->prof_ev[(size_t)4 * c->prof_n++];
     if (pe) HIP_TRY(c, hipEventRecord(pe[0], s));
     ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
-    const DevState *st_in = c->d_state + c->cur;
-    DevState *st_out = c->d_state + (c->cur ^ 1);
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
     int f_regs = 0;
     const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag, &f_regs) : nullptr;
@@ -853,15 +858,11 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.numel = c->d_numel;
         fa.ptrs = d_ptrs;
         fa.partials = c->d_partials;
-        fa.st_in = st_in;
-        fa.st_out = st_out;
+        fa.book = c->d_book;
         fa.lr = c->d_lr;
-        fa.barrier = c->d_barrier;
-        fa.barrier_target = (c->fused_launches + 1) * (unsigned long long)c->f_grid;
-        if (c->fail_next && !lag) fa.barrier_target += 1;  // adascale_fail_next_barrier: an arrival that never comes
+        fa.barrier_extra = c->fail_next && !lag ? 1 : 0;  // adascale_fail_next_barrier: an arrival that never comes
         c->fail_next = false;
         fa.spin_limit = c->tun.barrier_spin_limit > 0 ? c->tun.barrier_spin_limit : kFSpinLimit;
-        fa.fault = c->d_fault;
         fa.n_tiles = (int)c->ftiles.size();
         fa.tiles_per_block = c->f_tpb;
         fa.lds_tiles = f_lds_tiles;
@@ -877,6 +878,10 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
         if (c->cfg.flags & ADASCALE_COOPERATIVE_LAUNCH) {
             HIP_TRY(c, hipLaunchCooperativeKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args, lds_bytes, s));
+        } else if (capturing) {
+            // a replay is ordered by the graph's own dependencies; keeping it apart from fused steps
+            // on other streams is then the caller's business
+            HIP_TRY(c, hipLaunchKernel(fused_fn, dim3(c->f_grid), dim3(kFThreads), args, lds_bytes, s));
         } else {
             // Ordinary launch (a cooperative one costs ~15 us more per step here).  The grid is one
             // workgroup per CU, so all of it becomes resident as soon as the CUs are free; what
@@ -892,14 +897,12 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             ch.used = true;
             ch.last_stream = s;
         }
-        c->fused_launches += 1;
         if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
         if (lag) {
-            hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->f_grid, st_in, st_out,
-                               c->d_lr, sa);
+            hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->f_grid, c->d_book, c->d_lr,
+                               sa);
             HIP_TRY(c, hipGetLastError());
         }
-        c->cur ^= 1;
         if (pe)
             for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
         return ADASCALE_OK;
@@ -914,8 +917,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.numel = c->d_numel;
         ra.ptrs = d_ptrs;
         ra.partials = c->d_partials;
-        ra.claim = c->d_claim + (c->stream_launches & 1);
-        ra.claim_next = c->d_claim + ((c->stream_launches + 1) & 1);
+        ra.claim = &c->d_book->claim;
         ra.n_tiles = (int)c->ftiles.size();
         ra.n_cold = (int)c->ctiles.size();
         ra.S = S;
@@ -928,7 +930,6 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.inv_S = 1.0 / (double)S;
         void *args[] = {&ra};
         HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));
-        c->stream_launches += 1;
         n_partials = c->s_grid + (ra.n_tiles + 1) / 2;
     }
     // Prior-iteration gain without the streaming kernel: single pass (reduce + update), then the
@@ -936,15 +937,13 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     // averages and k_update applies it.
     if (lag && !stream_fn) {
         if (grid > 0) {
-            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, d_ptrs, grid, s, S, st_in, sa);
-            else launch_reduce_update<Bf16>(c, d_ptrs, grid, s, S, st_in, sa);
+            if (c->cfg.grad_dtype == ADASCALE_F32) launch_reduce_update<float>(c, d_ptrs, grid, s, S, sa);
+            else launch_reduce_update<Bf16>(c, d_ptrs, grid, s, S, sa);
             HIP_TRY(c, hipGetLastError());
         }
         if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-        hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, st_in, st_out,
-                           c->d_lr, sa);
+        hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, c->d_book, c->d_lr, sa);
         HIP_TRY(c, hipGetLastError());
-        c->cur ^= 1;
         if (pe)
             for (int j = 2; j < 4; ++j) HIP_TRY(c, hipEventRecord(pe[j], s));
         return ADASCALE_OK;
@@ -955,20 +954,18 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         HIP_TRY(c, hipGetLastError());
     }
     if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, st_in, st_out,
-                       c->d_lr, sa);
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, n_partials, c->d_book, c->d_lr, sa);
     HIP_TRY(c, hipGetLastError());
-    c->cur ^= 1;
     if (pe) HIP_TRY(c, hipEventRecord(pe[2], s));
     if (grid > 0) {
         const float rho = (float)c->cfg.momentum, lambda = (float)c->cfg.weight_decay;
 #define LAUNCH(VV)                                                                                       \
     hipLaunchKernelGGL((k_update<VV>), dim3(grid), dim3(kThreads), 0, s, c->d_span_first, c->d_tile_prefix, \
-                       c->d_numel, d_ptrs, st_out, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,     \
+                       c->d_numel, d_ptrs, c->d_book, c->n_tiles, c->span_tiles, c->n_spans, row_len, rho,  \
                        lambda)
         if (stream_fn && c->stream_momentum) {
-            ApplyArgs aa{c->d_ftiles, c->d_ctiles, c->d_numel, d_ptrs, st_out, (int)c->ftiles.size(), (int)c->ctiles.size(),
-                         row_len};
+            ApplyArgs aa{c->d_ftiles, c->d_ctiles, c->d_numel, d_ptrs, c->d_book, (int)c->ftiles.size(),
+                         (int)c->ctiles.size(), row_len};
             hipLaunchKernelGGL(k_apply, dim3(c->s_grid), dim3(kFThreads), 0, s, aa);
         } else {
             if (c->vec == 4) LAUNCH(4);
@@ -1060,8 +1057,7 @@ int adascale_step_flat(const adascale_flat_step *a, void *hip_stream)
         else LAUNCH(Bf16, 1);
     }
 #undef LAUNCH
-    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, &sc->partials[0][0], grid, &sc->st[0], &sc->st[1],
-                       a->lr_table, sa);
+    hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, &sc->partials[0][0], grid, &sc->book, a->lr_table, sa);
     if (vec == 4) hipLaunchKernelGGL(k_flat_finish<4>, dim3(grid), dim3(kThreads), 0, s, sc, (long long)a->numel, n_tiles, user);
     else hipLaunchKernelGGL(k_flat_finish<8>, dim3(grid), dim3(kThreads), 0, s, sc, (long long)a->numel, n_tiles, user);
     HIP_TRY(nullptr, hipGetLastError());

@@ -41,6 +41,27 @@ struct DevState {
     int done;
 };
 
+// Everything about a context's progress that changes from one launch to the next lives on the
+// device, in this record, and the kernels advance it themselves.  The host passes the same kernel
+// arguments at every step, so a step captured into a HIP graph can be replayed.
+struct DevBook {
+    // Steps completed.  State record st[epoch & 1] is the current one; a step reads it, writes
+    // the other record and then raises epoch (the kernel that evaluates the scalars does).
+    alignas(128) unsigned long long epoch;
+    // Fused launches with a grid barrier so far: the arrival counter stands at barrier_gen * grid
+    // between launches, and a launch waits for (barrier_gen + 1) * grid.
+    unsigned long long barrier_gen;
+    alignas(128) unsigned long long barrier;  // arrivals, monotonically increasing
+    alignas(128) int fault;                   // raised when a bounded wait at the barrier gave up
+    alignas(128) unsigned claim;              // streaming reduce: tile pairs handed out (zero between launches)
+    alignas(128) DevState st[2];
+};
+
+__device__ __forceinline__ unsigned long long book_epoch(const DevBook *bk)
+{
+    return __hip_atomic_load(&bk->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 // Same vectors with element alignment only: tensors inside flat buffers start anywhere.
@@ -319,14 +340,21 @@ struct ScalarIn {
     float lr_now;
 };
 
-__device__ __forceinline__ ScalarIn load_scalar_in(const DevState *__restrict__ in, const float *__restrict__ lr,
-                                                   const ScalarArgs &c)
+// Which record is current is itself read from memory (the epoch): both records are fetched
+// beside it and the choice is made in registers, one memory latency instead of two in a row.
+__device__ __forceinline__ ScalarIn load_scalar_in(const DevBook *__restrict__ book, const float *__restrict__ lr,
+                                                   const ScalarArgs &c, unsigned long long &epoch)
 {
+    epoch = book_epoch(book);
+    const DevState &r0 = book->st[0], &r1 = book->st[1];
+    const long long step0 = r0.step, step1 = r1.step;
+    const double tau0 = r0.tau, tau1 = r1.tau, sb0 = r0.sig_bar, sb1 = r1.sig_bar, mb0 = r0.mu_bar, mb1 = r1.mu_bar;
+    const bool odd = (epoch & 1) != 0;
     ScalarIn s;
-    s.step = in->step;
-    s.tau = in->tau;
-    s.sig_bar = in->sig_bar;
-    s.mu_bar = in->mu_bar;
+    s.step = odd ? step1 : step0;
+    s.tau = odd ? tau1 : tau0;
+    s.sig_bar = odd ? sb1 : sb0;
+    s.mu_bar = odd ? mb1 : mb0;
     long long idx = (long long)floor(s.tau);
     if (idx > c.L - 1) idx = c.L - 1;
     if (idx < 0) idx = 0;
@@ -389,14 +417,14 @@ __device__ __forceinline__ float eval_scalars(double A, double B, const ScalarIn
 constexpr int kScalarThreads = 1024;
 
 __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__restrict__ partials, int n_partials,
-                                                            const DevState *__restrict__ st_in,
-                                                            DevState *__restrict__ st_out,
+                                                            DevBook *__restrict__ book,
                                                             const float *__restrict__ lr, ScalarArgs c)
 {
     __shared__ double sh_a[kScalarThreads], sh_b[kScalarThreads];
     const int tid = threadIdx.x;
     ScalarIn sin{};
-    if (tid == 0) sin = load_scalar_in(st_in, lr, c);  // in flight while the partials are summed
+    unsigned long long epoch = 0;
+    if (tid == 0) sin = load_scalar_in(book, lr, c, epoch);  // in flight while the partials are summed
     typedef double d2 __attribute__((ext_vector_type(2)));
     const d2 *p2 = reinterpret_cast<const d2 *>(partials);
     double a = 0.0, b = 0.0;
@@ -424,19 +452,23 @@ __global__ __launch_bounds__(kScalarThreads) void k_scalars(const double *__rest
         }
         __syncthreads();
     }
-    if (tid == 0) eval_scalars(sh_a[0], sh_b[0], sin, st_out, c, true);
+    if (tid == 0) {
+        eval_scalars(sh_a[0], sh_b[0], sin, &book->st[(epoch + 1) & 1], c, true);
+        // the streaming reduce kernel of this step, if any, has finished with its counter
+        __hip_atomic_store(&book->claim, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&book->epoch, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // eta_t of the prior-iteration variant (App. B.3): r_t from the averages as they stand before
 // the step (r_0 = 1), so it is known before any gradient is read.
-__device__ __forceinline__ float lagged_eta(const DevState *__restrict__ st, const float *__restrict__ lr,
+__device__ __forceinline__ float lagged_eta(const DevBook *__restrict__ book, const float *__restrict__ lr,
                                             const ScalarArgs &c)
 {
-    const double r = st->step == 0 ? 1.0 : gain_from(c, st->sig_bar, st->mu_bar);
-    long long idx = (long long)floor(st->tau);
-    if (idx > c.L - 1) idx = c.L - 1;
-    if (idx < 0) idx = 0;
-    return (float)(r * (double)lr[idx]);
+    unsigned long long epoch;
+    const ScalarIn in = load_scalar_in(book, lr, c, epoch);
+    const double r = in.step == 0 ? 1.0 : gain_from(c, in.sig_bar, in.mu_bar);
+    return (float)(r * (double)in.lr_now);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -448,7 +480,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restric
                                                             const long long *__restrict__ numel,
                                                             const unsigned long long *__restrict__ ptrs,
                                                             double *__restrict__ partials,
-                                                            const DevState *__restrict__ st,
+                                                            const DevBook *__restrict__ book,
                                                             const float *__restrict__ lr, ScalarArgs sc, int n_tiles,
                                                             int span_tiles, int n_spans, int S, int row_len,
                                                             double inv_S, float rho, float lambda)
@@ -457,7 +489,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_update(const int *__restric
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
     __shared__ double sh[kWaves][2];
-    const float eta = lagged_eta(st, lr, sc);
+    const float eta = lagged_eta(book, lr, sc);  // k_scalars, behind this kernel, raises the epoch
 
     for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
         const int t0 = span * span_tiles;
@@ -508,12 +540,12 @@ __global__ __launch_bounds__(kThreads) void k_update(const int *__restrict__ spa
                                                      const int *__restrict__ tile_prefix,
                                                      const long long *__restrict__ numel,
                                                      const unsigned long long *__restrict__ ptrs,
-                                                     const DevState *__restrict__ st, int n_tiles, int span_tiles,
+                                                     const DevBook *__restrict__ book, int n_tiles, int span_tiles,
                                                      int n_spans, int row_len, float rho, float lambda)
 {
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
-    const float eta = st->eta_f32;
+    const float eta = book->st[book_epoch(book) & 1].eta_f32;  // the record k_scalars has just written
 
     for (int span = blockIdx.x; span < n_spans; span += gridDim.x) {
         const int t0 = span * span_tiles;
@@ -825,13 +857,10 @@ struct FusedArgs {
     const long long *numel;
     const unsigned long long *ptrs;
     double *partials;              // [gridDim.x][2]
-    const DevState *st_in;
-    DevState *st_out;
+    DevBook *book;                 // state records, epoch, barrier counter and generation, fault flag
     const float *lr;
-    unsigned long long *barrier;   // monotonically increasing arrival counter
-    unsigned long long barrier_target;
     long long spin_limit;          // polls after which the wait at the barrier gives up
-    int *fault;                    // set when the bounded wait at the barrier gave up
+    int barrier_extra;             // test hook: arrivals to wait for beyond the grid's (they never come)
     int n_tiles, n_cold, tiles_per_block, lds_tiles, S, row_len;
     int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
@@ -1054,7 +1083,7 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
             for (int w = 1; w < kFWaves; ++w) t += red[w][tid];
             p.partials[(size_t)b * 2 + tid] = t;
         }
-        eta = lagged_eta(p.st_in, p.lr, p.sc);
+        eta = lagged_eta(p.book, p.lr, p.sc);  // k_scalars, behind this kernel, raises the epoch
     } else {
         // The partials cross workgroups (and XCDs, whose L2s are not coherent with each other): they
         // are written and read with agent-scope atomic accesses, which are performed at the memory
@@ -1063,8 +1092,15 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         // phase 1 (scratch tiles) is read by another workgroup.
         // (the state of before the step and lr(floor(tau_t)) do not depend on the sums: lane 0
         // fetches them here, behind the wait for the partial store and for the other workgroups)
+        // So are the epoch (which state record is current) and the barrier's generation: workgroup 0
+        // raises both after the barrier, that is after this workgroup has arrived.
         ScalarIn sin{};
-        if (tid == 0) sin = load_scalar_in(p.st_in, p.lr, p.sc);
+        unsigned long long epoch = 0, barrier_target = 0;
+        if (tid == 0) {
+            const unsigned long long gen = __hip_atomic_load(&p.book->barrier_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sin = load_scalar_in(p.book, p.lr, p.sc, epoch);
+            barrier_target = (gen + 1) * (unsigned long long)G + (unsigned long long)p.barrier_extra;
+        }
         if (tid < 2) {
             double t = red[0][tid];
     #pragma unroll
@@ -1082,21 +1118,28 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         // reports the step as failed either way.)
         __syncthreads();
         if (tid == 0) {
-            __hip_atomic_fetch_add(p.barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(&p.book->barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             long long spins = 0;
             int failed = 0;
             for (;;) {
-                const unsigned long long seen = __hip_atomic_load(p.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                failed = __hip_atomic_load(p.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (failed || seen >= p.barrier_target) break;
+                const unsigned long long seen = __hip_atomic_load(&p.book->barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                failed = __hip_atomic_load(&p.book->fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (failed || seen >= barrier_target) break;
                 if (++spins > p.spin_limit) {
-                    __hip_atomic_store(p.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&p.book->fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     failed = 1;
                     break;
                 }
                 __builtin_amdgcn_s_sleep(16);  // poll not too often: 256 pollers share one address
             }
             sh_fault = failed;
+            // The counter receives this grid's arrivals whatever happens (a workgroup that gives up
+            // has arrived; one that was not resident arrives when it runs), so the generation moves
+            // on with it even when the step is void.
+            if (b == 0) {
+                const unsigned long long gen = (barrier_target - (unsigned long long)p.barrier_extra) / (unsigned long long)G;
+                __hip_atomic_store(&p.book->barrier_gen, gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         __syncthreads();
         if (sh_fault) return;
@@ -1115,7 +1158,10 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
             }
             __syncthreads();
         }
-        if (tid == 0) sh_eta = eval_scalars(red[0][0], red[0][1], sin, p.st_out, p.sc, b == 0);
+        if (tid == 0) {
+            sh_eta = eval_scalars(red[0][0], red[0][1], sin, &p.book->st[(epoch + 1) & 1], p.sc, b == 0);
+            if (b == 0) __hip_atomic_store(&p.book->epoch, epoch + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         __syncthreads();
         eta = sh_eta;
     }
@@ -1149,8 +1195,7 @@ struct StreamArgs {
     const long long *numel;
     const unsigned long long *ptrs;
     double *partials;              // [gridDim.x + pairs][2]
-    unsigned *claim;               // pairs handed out so far in this launch (zero on entry)
-    unsigned *claim_next;          // the next launch's counter: zeroed here
+    unsigned *claim;               // pairs handed out so far in this launch (zero on entry; k_scalars zeroes it again)
     int n_tiles, n_cold, S, row_len;
     int nh;                        // half-groups per tile (used by the instances with NH = 0)
     double inv_S;
@@ -1199,7 +1244,6 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
     };
     int pend = -1;  // lane 0: the pair after the next one
     if (tid == 0) {
-        if (b == 0) *p.claim_next = 0u;
         s_claim[0] = claim();
         s_claim[1] = claim();
         pend = claim();
@@ -1316,10 +1360,11 @@ __global__ __launch_bounds__(kFThreads) void k_reduce_stream(StreamArgs p)
 
 // Also lowers the fault flag a fused step raises when its grid barrier gives up: the caller has
 // restored w, v and this state from a checkpoint.
-__global__ void k_set_state(DevState *st, long long step, double tau, double sbar, double mbar, long long L, int *fault)
+__global__ void k_set_state(DevBook *book, long long step, double tau, double sbar, double mbar, long long L)
 {
     if (threadIdx.x == 0 && blockIdx.x == 0) {
-        *fault = 0;
+        DevState *st = &book->st[book_epoch(book) & 1];
+        book->fault = 0;
         st->step = step;
         st->tau = tau;
         st->sig_bar = sbar;
@@ -1341,7 +1386,7 @@ struct ApplyArgs {
     const FTile *tiles, *cold;     // full and ragged tiles, read through the constant address space
     const long long *numel;
     const unsigned long long *ptrs;
-    const DevState *st;
+    const DevBook *book;
     int n_tiles, n_cold, row_len;
 };
 
@@ -1352,7 +1397,7 @@ __global__ __launch_bounds__(kFThreads) void k_apply(ApplyArgs p)
     constexpr int U = kApplyRound;
     const int tid = threadIdx.x, b = blockIdx.x, G = gridDim.x;
     const unsigned lane_off = (unsigned)tid * 16u;
-    const float eta = p.st->eta_f32;
+    const float eta = p.book->st[book_epoch(p.book) & 1].eta_f32;  // the record k_scalars has just written
     auto locate = [&](int t) -> FLoc {
         const AS_CONST int *tp = (const AS_CONST int *)p.tiles + 2 * (size_t)t;
         return FLoc{(cp_u64)p.ptrs + (size_t)tp[0] * p.row_len, (unsigned long long)tp[1] * (kFTile * 4ULL)};
@@ -1404,7 +1449,7 @@ constexpr int kFlatMaxGrid = 2048;    // workgroups of the sweep = partial slots
 
 struct FlatScratch {
     unsigned long long row[kRowG + kFlatMaxScale];  // [w, v, unused, g_0 .. g_{S-1}]
-    DevState st[2];                                 // before / after the step
+    DevBook book;                                   // st[0] / st[1]: before / after the step
     alignas(16) double partials[kFlatMaxGrid][2];   // k_scalars reads them as pairs
 };
 
@@ -1413,8 +1458,9 @@ struct FlatPointers {
 };
 
 // The block keeps whatever the last call left in it: everything a call reads is written here or
-// by its own sweep first (pointer row, the state record of before the step, and -- by the sweep --
-// exactly the partial slots k_scalars is told to add).
+// by its own sweep first (pointer row, the epoch -- zero, so that k_scalars reads record 0 and
+// writes record 1 --, the state record of before the step, and, by the sweep, exactly the partial
+// slots k_scalars is told to add).
 __global__ void k_flat_setup(FlatScratch *sc, FlatPointers ptrs, int S, const adascale_state *user)
 {
     const int tid = threadIdx.x;
@@ -1427,7 +1473,8 @@ __global__ void k_flat_setup(FlatScratch *sc, FlatPointers ptrs, int S, const ad
         st.tau = user->tau;
         st.sig_bar = user->sigma2_bar;
         st.mu_bar = user->mu2_bar;
-        sc->st[0] = st;
+        sc->book.epoch = 0;
+        sc->book.st[0] = st;
     }
     if (tid < S) sc->row[kRowG + tid] = ptrs.g[tid];
 }
@@ -1472,7 +1519,7 @@ __global__ __launch_bounds__(kThreads) void k_flat_finish(const FlatScratch *sc,
 {
     constexpr int TILE = kThreads * VEC;
     const int tid = threadIdx.x;
-    const DevState &st = sc->st[1];
+    const DevState &st = sc->book.st[1];
     const float eta = st.eta_f32;
     float *wp = reinterpret_cast<float *>(sc->row[kRowW]);
     const float *vp = reinterpret_cast<const float *>(sc->row[kRowV]);
