@@ -522,6 +522,55 @@ def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, step_path):
     H.assert_report(H.run_teacher_forced(wl, log=log))
 
 
+@pytest.mark.timeout(600)
+def test_one_tensor_beyond_two_to_the_31_elements(step_path):
+    """Maximum sizes: a single tensor of 2^31 + 6149 elements (element offsets beyond 32 bits, byte
+    offsets beyond 2^33, a ragged last tile), S = 2 bf16 gradients.  The oracle takes the tensor
+    in chunks through its C entry points (the norms are global, so chunks are just more tensors
+    to it); w and v are compared element by element on the first chunk, the two chunks around
+    element 2^31 and the last one, the scalars on everything."""
+    import ctypes
+    from oracle.oracle import Oracle
+    n = 2 ** 31 + 3 * 2048 + 5
+    wl = W.custom([(n,)], 2, grad_dtype=BF16, weight_decay=1e-4, theta=0.0, lr_table=W.lr_constant(0.05), steps=1, seed=17)
+    inp = W.Inputs(wl, "cuda:0")
+    inp.fill_grads(0)
+    gpu = H.make_gpu(wl)
+    chunk = 1 << 26
+    bounds = [(lo, min(lo + chunk, n)) for lo in range(0, n, chunk)]
+    sampled = sorted({0, 2 ** 31 // chunk - 1, 2 ** 31 // chunk, len(bounds) - 1})
+    before = {c: (inp.w_flat[lo:hi].cpu().numpy().astype(np.float64), inp.v_flat[lo:hi].cpu().numpy().astype(np.float64))
+              for c in sampled for lo, hi in [bounds[c]]}
+    gpu.step(inp.w, inp.v, inp.g)
+    got = gpu.get_state()
+    log(f"path {gpu.step_path()}: r={got.r:.6g} A={got.sum_sq:.6g} B={got.sq_mean:.6g}")
+
+    orc = Oracle(wl.S, wl.lr_table, wl.momentum, wl.weight_decay, wl.theta, wl.eps, wl.grad_dtype, 0, openmp=True)
+    lib, h = orc._l, orc._h
+    lib.oracle_begin_step(h)
+    gbar = {}
+    for c, (lo, hi) in enumerate(bounds):
+        rows = [inp.g_flat[i][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16) for i in range(wl.S)]
+        ptrs = (ctypes.c_void_p * wl.S)(*[r.ctypes.data for r in rows])
+        gb = np.empty(hi - lo, dtype=np.float64)
+        lib.oracle_accumulate(h, hi - lo, ptrs, gb.ctypes.data)
+        if c in sampled:
+            gbar[c] = gb
+    lib.oracle_gain(h)
+    for c in sampled:
+        lo, hi = bounds[c]
+        w64, v64 = before[c]
+        lib.oracle_apply(h, hi - lo, w64.ctypes.data, v64.ctypes.data, gbar[c].ctypes.data)
+        for name, flat, ref in (("w", inp.w_flat, w64), ("v", inp.v_flat, v64)):
+            err = np.abs(flat[lo:hi].cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max()
+            log(f"chunk {c} [{lo}, {hi}): {name} err {err:.3g}")
+            assert err <= H.TOL_W, (c, name, err)
+    lib.oracle_advance(h)
+    rel = H.compare_step(got, orc.state(), wl.S)
+    assert max(v for k, v in rel.items() if not k.endswith("_plain")) <= H.TOL_SCALAR, rel
+    gpu.close()
+
+
 def _random_case(seed):
     rng = np.random.default_rng(seed)
     sizes = []
