@@ -571,6 +571,18 @@ def test_one_tensor_beyond_two_to_the_31_elements(step_path):
     gpu.close()
 
 
+@pytest.mark.parametrize("S,dtype", [(4096, BF16), (4095, F32), (1000, F32)])
+def test_largest_scales_of_the_512_lane_kernels(S, dtype, step_path):
+    """The run-time half-group count at its upper end: S = 4096 is the largest scale the fused and
+    streaming kernels take (512 half-groups of 8 bf16 loads, 1024 of 4 fp32 loads), 4095 and 1000
+    leave padding slots in the last pair of half-groups."""
+    wl = W.custom([(2048 * 3 + 77,), (5,), (2048,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5, steps=2, seed=S)
+    g = H.make_gpu(wl)
+    assert g.step_path() == {"fused": "fused", "three_kernel": "streaming", "general": "general"}[step_path]
+    g.close()
+    H.assert_report(H.run_teacher_forced(wl, log=log))
+
+
 def _random_case(seed):
     rng = np.random.default_rng(seed)
     sizes = []
