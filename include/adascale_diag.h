@@ -19,7 +19,7 @@ extern "C" {
  * choice depends on the gradient type, the scale of the moment and the size of the parameter
  * list, and on adascale_tuning when the context was created with one):
  *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient of Algorithm 1 on
- *                            chip as far as it fits (S <= 4096 and at least a fifth of the mean
+ *                            chip as far as it fits (S <= 4096 and at least a quarter of the mean
  *                            gradient fitting in registers + LDS);
  *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
  *                            sweep in memory order: S <= 4096, parameter lists far larger than
@@ -45,7 +45,7 @@ typedef struct {
     int32_t fused_max_grid;      /* > 0: at most this many workgroups in the fused step (fewer than compute
                                     units: forces tiles beyond the chip's capacity on small inputs) */
     int32_t fused_min_percent;   /* > 0: least share of the mean gradient on chip for the fused step
-                                    (default 20; ignored under ADASCALE_FORCE_FUSED) */
+                                    (default 25; ignored under ADASCALE_FORCE_FUSED) */
     int32_t stream_via_scratch;  /* 1: the streaming sweep writes the mean gradient to a scratch of d floats
                                     and the full update kernel follows, instead of leaving the new momentum
                                     in v (12 instead of 8 bytes written per parameter) */

@@ -267,7 +267,7 @@ const void *stream_kernel_for(int dtype, int S)
 // Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
 // so that its workgroups (one per CU in number) also land one per CU.
 constexpr size_t kStreamLdsPad = 96 * 1024;
-constexpr int kFusedMinPct = 20;  // least share of the mean gradient on chip for the fused step
+constexpr int kFusedMinPct = 25;  // least share of the mean gradient on chip for the fused step
 
 // ---- planning: pure host arithmetic (no HIP calls), shared by the set-up below and adascale_plan ----
 
@@ -322,7 +322,8 @@ FusedPlan plan_fused(const adascale_tuning &tun, long long nt, long long nc, int
         if (fused_regs_at(l) <= nt / f.grid) f.level = l;
     f.lds_cap = lds_per_workgroup > 6144 ? (int)((lds_per_workgroup - 6144) / (kFThreads * sizeof(f4))) : 0;  // static LDS is ~4.2 KB
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
-    // kernel is the faster one (measured crossover: 13-25 % on chip, depending on S and gradient type)
+    // kernel is the faster one (measured crossover: 22-36 % on chip, depending on S and gradient type;
+    // within 3 % of each other from 20 to 37 %)
     f.on_chip_pct = f.tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(f.level) + std::min(f.tpb, f.lds_cap)) / f.tpb);
     const int min_pct = tun.force_path == ADASCALE_FORCE_FUSED ? 0 : tun.fused_min_percent > 0 ? tun.fused_min_percent : kFusedMinPct;
     if (stream_ok && f.on_chip_pct < min_pct) return f;

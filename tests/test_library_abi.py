@@ -128,7 +128,7 @@ def test_plan_of_the_benchmark_configurations():
             assert p["register_tiles"] + p["lds_tiles"] <= p["tiles_per_workgroup"]
             assert 0 <= p["lds_tiles"] <= 19                                                   # 19 tiles of 8 KB fit beside the static LDS
             kept = min(p["tiles_per_workgroup"], p["register_tiles"] + p["lds_tiles"])
-            assert p["on_chip_percent"] == min(100, 100 * kept // p["tiles_per_workgroup"]) >= 20
+            assert p["on_chip_percent"] == min(100, 100 * kept // p["tiles_per_workgroup"]) >= 25
     p3, p4 = binding.plan(W.config(3).numel, 16), binding.plan(W.config(4).numel, 32, binding.BF16)
     assert (p3["register_tiles"], p3["on_chip_percent"]) == (44, 100)
     assert (p4["register_tiles"], p4["lds_tiles"], p4["tiles_per_workgroup"], p4["on_chip_percent"]) == (44, 19, 116, 54)
@@ -140,7 +140,7 @@ def test_plan_of_the_benchmark_configurations():
     assert binding.plan(W.config(3).numel, 16, tuning=T(force_path=binding.FORCE_STREAMING))["path"] == "streaming"
     assert binding.plan(W.config(3).numel, 16, tuning=T(force_path=binding.FORCE_GENERAL))["path"] == "general"
     forced = binding.plan(W.config(5).numel, 64, binding.BF16, tuning=T(force_path=binding.FORCE_FUSED))
-    assert forced["path"] == "fused" and forced["on_chip_percent"] < 20
+    assert forced["path"] == "fused" and forced["on_chip_percent"] < 25
     assert binding.plan(W.config(4).numel, 32, binding.BF16, tuning=T(fused_min_percent=60))["path"] == "streaming"
     assert binding.plan(W.config(5).numel, 64, binding.BF16, tuning=T(fused_min_percent=5))["path"] == "fused"
     few = binding.plan(W.config(1).numel, 4, tuning=T(fused_max_grid=2))
