@@ -823,12 +823,11 @@ __device__ __forceinline__ f4 fused_tile_mean(const FLoc &cur, const FLoc &next,
 // parameters that are cold at the start of a step: cfg3 319.6 -> 307.4 us, cfg2 98.4 -> 96.0 us,
 // cfg4 (with fused_tile_apply) 780.5 -> 759.5 us.  (A loop that steps on the same 204 MB of w, v
 // again and again, and so finds them cached, is 1 % slower for it at cfg3.)
-__device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_off, f4 g, float eta, float rho,
+__device__ __forceinline__ void fused_tile_finish(const FLoc &L, unsigned lane_off, f4 wv, f4 vv, f4 g, float eta, float rho,
                                                   float lambda)
 {
     gp_char w = (gp_char)(L.row[kRowW] + L.tile_off) + lane_off;
     gp_char v = (gp_char)(L.row[kRowV] + L.tile_off) + lane_off;
-    const f4 wv = __builtin_nontemporal_load((gp_cf4)w), vv = __builtin_nontemporal_load((gp_cf4)v);
     const float gv[4] = {g.x, g.y, g.z, g.w};
     float wn[4] = {wv.x, wv.y, wv.z, wv.w}, vn[4] = {vv.x, vv.y, vv.z, vv.w};
 #pragma unroll
@@ -839,6 +838,14 @@ __device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_o
     }
     __builtin_nontemporal_store(f4{vn[0], vn[1], vn[2], vn[3]}, (gp_f4)v);
     __builtin_nontemporal_store(f4{wn[0], wn[1], wn[2], wn[3]}, (gp_f4)w);
+}
+
+__device__ __forceinline__ void fused_tile_update(const FLoc &L, unsigned lane_off, f4 g, float eta, float rho,
+                                                  float lambda)
+{
+    const f4 wv = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowW] + L.tile_off) + lane_off));
+    const f4 vv = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off));
+    fused_tile_finish(L, lane_off, wv, vv, g, eta, rho, lambda);
 }
 
 // w <- w - eta v for one full tile whose new momentum is already in v.
@@ -1067,6 +1074,25 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         fused_regs_phase1<GT, HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 
+    // Small parameter lists (a few tiles per workgroup, none in registers) are bound by latency, not
+    // by bandwidth: w and v of up to kFPrefetch LDS-held tiles are requested here, ahead of the grid
+    // barrier, so that phase 2 finds them in registers.
+    constexpr int kFPrefetch = 4;
+    f4 pre_w[kFPrefetch], pre_v[kFPrefetch];
+    const bool prefetched = R == 0 && !LAG && p.tiles_per_block <= kFPrefetch && q_hbm >= n_valid;
+    if constexpr (R == 0 && !LAG) {
+        if (prefetched) {
+#pragma unroll
+            for (int q = 0; q < kFPrefetch; ++q) {
+                if (q < q_lds_end) {
+                    const FLoc L = cx.locate(q);
+                    pre_w[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowW] + L.tile_off) + lane_off));
+                    pre_v[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off));
+                }
+            }
+        }
+    }
+
     // workgroup partial -> fixed slot
     acc_a = wave_sum(acc_a);
     acc_b = wave_sum(acc_b);
@@ -1167,7 +1193,15 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
     }
     // phase 2: momentum update from the retained mean gradient
     if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
-    for (int q = R; q < q_lds_end; ++q)
+    if constexpr (R == 0 && !LAG) {
+        if (prefetched) {
+#pragma unroll
+            for (int q = 0; q < kFPrefetch; ++q)
+                if (q < q_lds_end)
+                    fused_tile_finish(cx.locate(q), lane_off, pre_w[q], pre_v[q], lds_gbar[q * kFThreads + tid], eta, p.rho, p.lambda);
+        }
+    }
+    for (int q = prefetched ? q_lds_end : R; q < q_lds_end; ++q)
         fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
     for (int q = q_hbm; q < n_valid; ++q) fused_tile_apply(cx.locate(q), lane_off, eta);
     for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);  // same owner as in phase 1
