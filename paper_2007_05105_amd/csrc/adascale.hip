@@ -317,10 +317,15 @@ FusedPlan plan_fused(const adascale_tuning &tun, long long nt, long long nc, int
     const int cus = std::min(std::min(cus_of_device, kFMaxGrid), tun.fused_max_grid > 0 ? tun.fused_max_grid : kFMaxGrid);
     f.grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
     f.tpb = (int)((nt + f.grid - 1) / f.grid);
-    // register-slot level: the highest whose slot count every workgroup can fill
-    for (int l = 0; l < kFRegLevels; ++l)
-        if (fused_regs_at(l) <= nt / f.grid) f.level = l;
     f.lds_cap = lds_per_workgroup > 6144 ? (int)((lds_per_workgroup - 6144) / (kFThreads * sizeof(f4))) : 0;  // static LDS is ~4.2 KB
+    // Register-slot level: among those whose slot count every workgroup can fill, the lowest that,
+    // with the LDS, still holds every tile of a workgroup (the registers it leaves free take w and
+    // v of more tiles ahead of the grid barrier), else the highest.
+    for (int l = 0; l < kFRegLevels; ++l) {
+        if (fused_regs_at(l) > nt / f.grid) break;
+        f.level = l;
+        if (fused_regs_at(l) + f.lds_cap >= f.tpb) break;
+    }
     // with little of the mean gradient on chip the three-kernel step with the streaming reduce
     // kernel is the faster one (measured crossover: 22-36 % on chip, depending on S and gradient type;
     // within 3 % of each other from 20 to 37 %)

@@ -1074,24 +1074,12 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         fused_regs_phase1<GT, HG, NH, MASK, R, 0>(cx, lane_off, keep, cur, xa, acc_a, acc_b);
     }
 
-    // Small parameter lists (a few tiles per workgroup, none in registers) are bound by latency, not
-    // by bandwidth: w and v of up to kFPrefetch LDS-held tiles are requested here, ahead of the grid
-    // barrier, so that phase 2 finds them in registers.
-    constexpr int kFPrefetch = 4;
-    f4 pre_w[kFPrefetch], pre_v[kFPrefetch];
-    const bool prefetched = R == 0 && !LAG && p.tiles_per_block <= kFPrefetch && q_hbm >= n_valid;
-    if constexpr (R == 0 && !LAG) {
-        if (prefetched) {
-#pragma unroll
-            for (int q = 0; q < kFPrefetch; ++q) {
-                if (q < q_lds_end) {
-                    const FLoc L = cx.locate(q);
-                    pre_w[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowW] + L.tile_off) + lane_off));
-                    pre_v[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off));
-                }
-            }
-        }
-    }
+    // w and v of the first kPre slots (register slots first, then LDS slots: the order of phase 2)
+    // are requested right after the workgroup has arrived at the grid barrier: the loads travel
+    // while it waits for the others, and phase 2 finds them in registers.  How many depends on the
+    // registers the instance has to spare (the load buffers of phase 1 are free again by then).
+    constexpr int kPre = LAG ? 0 : R == 0 ? 16 : R <= 10 ? 20 : R <= 30 ? 10 : 4;  // the most that leaves no spills
+    f4 pre_w[kPre > 0 ? kPre : 1], pre_v[kPre > 0 ? kPre : 1];
 
     // workgroup partial -> fixed slot
     acc_a = wave_sum(acc_a);
@@ -1143,8 +1131,18 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         // carry on; tiles beyond the chip's capacity already hold the new momentum in v.  The host
         // reports the step as failed either way.)
         __syncthreads();
+        if (tid == 0) __hip_atomic_fetch_add(&p.book->barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if constexpr (kPre > 0) {
+#pragma unroll
+            for (int q = 0; q < kPre; ++q) {
+                if (q < R || q < q_lds_end) {  // register slots always exist
+                    const FLoc L = cx.locate(q);
+                    pre_w[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowW] + L.tile_off) + lane_off));
+                    pre_v[q] = __builtin_nontemporal_load((gp_cf4)((gp_cchar)(L.row[kRowV] + L.tile_off) + lane_off));
+                }
+            }
+        }
         if (tid == 0) {
-            __hip_atomic_fetch_add(&p.book->barrier, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             long long spins = 0;
             int failed = 0;
             for (;;) {
@@ -1192,16 +1190,19 @@ __global__ __launch_bounds__(kFThreads) void k_fused(FusedArgs p)
         eta = sh_eta;
     }
     // phase 2: momentum update from the retained mean gradient
-    if (n_valid > 0) fused_regs_phase2<R, 0>(cx, lane_off, keep, eta);
-    if constexpr (R == 0 && !LAG) {
-        if (prefetched) {
+    if constexpr (kPre > 0) {
 #pragma unroll
-            for (int q = 0; q < kFPrefetch; ++q)
-                if (q < q_lds_end)
-                    fused_tile_finish(cx.locate(q), lane_off, pre_w[q], pre_v[q], lds_gbar[q * kFThreads + tid], eta, p.rho, p.lambda);
+        for (int q = 0; q < kPre; ++q) {
+            if (q < R) {
+                if (n_valid > 0) fused_tile_finish(cx.locate(q), lane_off, pre_w[q], pre_v[q], keep[q < R ? q : 0], eta, p.rho, p.lambda);
+            } else if (q < q_lds_end) {
+                fused_tile_finish(cx.locate(q), lane_off, pre_w[q], pre_v[q], lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
+            }
         }
     }
-    for (int q = prefetched ? q_lds_end : R; q < q_lds_end; ++q)
+    constexpr int kRegFrom = kPre < R ? kPre : R;
+    if (n_valid > 0) fused_regs_phase2<R, kRegFrom>(cx, lane_off, keep, eta);
+    for (int q = kPre > R ? kPre : R; q < q_lds_end; ++q)
         fused_tile_update(cx.locate(q), lane_off, lds_gbar[(q - R) * kFThreads + tid], eta, p.rho, p.lambda);
     for (int q = q_hbm; q < n_valid; ++q) fused_tile_apply(cx.locate(q), lane_off, eta);
     for (int c = G - 1 - b; c < p.n_cold; c += G) fused_cold_update(p, c, tid, eta);  // same owner as in phase 1
