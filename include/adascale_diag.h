@@ -19,11 +19,11 @@ extern "C" {
  * choice depends on the gradient type, the scale of the moment and the size of the parameter
  * list, and on adascale_tuning when the context was created with one):
  *   ADASCALE_PATH_FUSED      one persistent launch that keeps the mean gradient of Algorithm 1 on
- *                            chip as far as it fits (S <= 4096 and at least a quarter of the mean
- *                            gradient fitting in registers + LDS);
+ *                            chip as far as it fits (S <= 4096 and at least 8 % of the mean
+ *                            gradient fitting in registers + LDS: lists up to about 400 M
+ *                            parameters on MI355X);
  *   ADASCALE_PATH_STREAMING  three kernels (reduce, scalars, update), the first one a persistent
- *                            sweep in memory order: S <= 4096, parameter lists far larger than
- *                            the chip;
+ *                            sweep in memory order: S <= 4096, parameter lists beyond that;
  *   ADASCALE_PATH_GENERAL    three kernels for any scale (or two with ADASCALE_LAGGED_R: one
  *                            sweep that reduces and updates, then the scalars).
  */
@@ -45,12 +45,21 @@ typedef struct {
     int32_t fused_max_grid;      /* > 0: at most this many workgroups in the fused step (fewer than compute
                                     units: forces tiles beyond the chip's capacity on small inputs) */
     int32_t fused_min_percent;   /* > 0: least share of the mean gradient on chip for the fused step
-                                    (default 25; ignored under ADASCALE_FORCE_FUSED) */
+                                    (default 8; ignored under ADASCALE_FORCE_FUSED) */
     int32_t stream_via_scratch;  /* 1: the streaming sweep writes the mean gradient to a scratch of d floats
                                     and the full update kernel follows, instead of leaving the new momentum
                                     in v (12 instead of 8 bytes written per parameter) */
     int64_t barrier_spin_limit;  /* > 0: polls after which the fused step's grid barrier gives up
                                     (default 2^22, several seconds) */
+    int32_t burst_tiles;         /* sweeps that write as they read (the streaming sweep; the fused step on its
+                                    tiles beyond the chip's capacity) keep finished tiles in LDS and write them
+                                    in bursts that all workgroups issue in the same clock windows, from 32
+                                    gradient bytes per parameter (S x element size) upwards: < 0 no bursts
+                                    (every tile written at once), > 0 bursts at any scale, with at most this
+                                    many tiles kept by the streaming sweep (up to 18, the default) */
+    int32_t burst_window_ticks;  /* > 0: bursts at any scale, in windows of this many ticks of the device's
+                                    wall clock, 10 ns each on MI355X (default: from the scale, 0.8 x the time
+                                    the ring of kept tiles takes to fill) */
 } adascale_tuning;
 
 /* adascale_init with knobs; tuning == NULL is adascale_init. */

@@ -66,7 +66,8 @@ FLAT_MAX_NUMEL = (1 << 40) - 1
 class Tuning(C.Structure):
     """adascale_tuning: knobs for tests and measurements; all zero = the library's own choices."""
     _fields_ = [("force_path", C.c_int32), ("fused_max_grid", C.c_int32), ("fused_min_percent", C.c_int32),
-                ("stream_via_scratch", C.c_int32), ("barrier_spin_limit", C.c_int64)]
+                ("stream_via_scratch", C.c_int32), ("barrier_spin_limit", C.c_int64),
+                ("burst_tiles", C.c_int32), ("burst_window_ticks", C.c_int32)]
 
 
 class PlanInfo(C.Structure):

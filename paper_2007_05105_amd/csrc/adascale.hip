@@ -109,6 +109,9 @@ struct adascale_ctx {
     // streaming reduce (first kernel of the three-kernel step)
     bool tiles_ok = false, stream_ok = false;
     int n_cus = 0, s_grid = 0;
+    int s_keep = 0;                      // tiles the streaming sweep keeps in LDS between write bursts
+    size_t s_lds = 0;                    // its dynamic LDS
+    int wall_khz = 100000;               // rate of the clock the bursts are timed by
     bool stream_momentum = true;         // the sweep writes the new momentum instead of the mean gradient
 
     DevBook *h_book = nullptr;      // pinned
@@ -267,7 +270,7 @@ const void *stream_kernel_for(int dtype, int S)
 // Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
 // so that its workgroups (one per CU in number) also land one per CU.
 constexpr size_t kStreamLdsPad = 96 * 1024;
-constexpr int kFusedMinPct = 25;  // least share of the mean gradient on chip for the fused step
+constexpr int kFusedMinPct = 8;   // least share of the mean gradient on chip for the fused step
 
 // ---- planning: pure host arithmetic (no HIP calls), shared by the set-up below and adascale_plan ----
 
@@ -285,6 +288,29 @@ bool plan_tiles(const long long *numel, int N, long long *full, long long *ragge
     *full = nt;
     *ragged = nc;
     return true;
+}
+
+// Length of the clock windows in which a sweep writes its kept tiles (BurstRing), in ticks of the
+// device's wall clock: 0.8 of the time a workgroup takes to fill a ring of `keep` tiles when
+// `grid` workgroups sweep at 6.5 TB/s together, so that the ring is rarely full before a window
+// opens.  Returned as 2^64 / ticks, the factor the kernel turns a clock reading into a window
+// number with; 0 (no bursts) if there is no ring.
+unsigned long long burst_window_factor(const adascale_ctx *c, int S, int grid, int keep)
+{
+    if (keep <= 0 || c->tun.burst_tiles < 0) return 0;
+    const double b = c->cfg.grad_dtype == ADASCALE_F32 ? 4.0 : 2.0;
+    // With few gradient bytes per parameter the writes are too large a share of the sweep to be set
+    // apart: measured at d = 351 M, bursts cost 7-12 % at 2-16 gradient bytes per parameter, gain
+    // 0.7 % at 32, 4-7 % at 64, 6 % at 128.  (A knob that asks for bursts gets them at any scale.)
+    if (S * b < 32.0 && c->tun.burst_tiles == 0 && c->tun.burst_window_ticks <= 0) return 0;
+    double ticks = (double)c->tun.burst_window_ticks;
+    if (ticks <= 0) {
+        const double tile_bytes = (double)kFTile * (S * b + (c->cfg.weight_decay != 0.0 ? 12.0 : 8.0));
+        const double us_per_tile = tile_bytes * std::max(1, grid) / 6.5e6;
+        ticks = 0.8 * keep * us_per_tile * c->wall_khz / 1000.0;
+    }
+    ticks = std::min(std::max(ticks, 64.0), 1e9);
+    return (unsigned long long)(18446744073709551616.0 / ticks);
 }
 
 // May the streaming reduce kernel run on this device at all (its grid: plan_stream_grid)?
@@ -317,7 +343,7 @@ FusedPlan plan_fused(const adascale_tuning &tun, long long nt, long long nc, int
     const int cus = std::min(std::min(cus_of_device, kFMaxGrid), tun.fused_max_grid > 0 ? tun.fused_max_grid : kFMaxGrid);
     f.grid = (int)std::max<long long>(1, std::min<long long>(std::max(nt, nc), cus));
     f.tpb = (int)((nt + f.grid - 1) / f.grid);
-    f.lds_cap = lds_per_workgroup > 6144 ? (int)((lds_per_workgroup - 6144) / (kFThreads * sizeof(f4))) : 0;  // static LDS is ~4.2 KB
+    f.lds_cap = lds_per_workgroup > 6144 ? (int)((lds_per_workgroup - 6144) / (kFThreads * sizeof(f4))) : 0;  // static LDS is 5.3 KB
     // Register-slot level: among those whose slot count every workgroup can fill, the lowest that,
     // with the LDS, still holds every tile of a workgroup (the registers it leaves free take w and
     // v of more tiles ahead of the grid barrier), else the highest.
@@ -345,6 +371,14 @@ int setup_tiles(adascale_ctx *c)
     hipDeviceProp_t prop;
     HIP_TRY(c, hipGetDeviceProperties(&prop, c->cfg.device));
     c->n_cus = prop.multiProcessorCount;
+    {
+        int khz = 0;  // the clock the write bursts are timed by
+        if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->cfg.device) != hipSuccess || khz <= 0) {
+            (void)hipGetLastError();
+            khz = 100000;
+        }
+        c->wall_khz = khz;
+    }
     const int N = (int)c->numel.size();
     long long full = 0, ragged = 0;
     if (!plan_tiles(c->numel.data(), N, &full, &ragged)) return ADASCALE_OK;
@@ -373,10 +407,16 @@ int setup_tiles(adascale_ctx *c)
 
     if (!plan_stream_ok(c->tun, prop.sharedMemPerBlock)) return ADASCALE_OK;
     c->s_grid = plan_stream_grid((long long)nt, (long long)nc, c->n_cus);
+    {
+        const int cap = (int)std::min<size_t>(kStreamKeepMax, (prop.sharedMemPerBlock - 2048) / (kFThreads * sizeof(f4)));
+        const int want = c->tun.burst_tiles;
+        c->s_keep = want < 0 ? 0 : std::min(cap, want > 0 ? want : kStreamKeepMax);
+        c->s_lds = std::max(kStreamLdsPad, (size_t)c->s_keep * kFThreads * sizeof(f4));
+    }
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
         const void *fn = stream_kernel_for(c->cfg.grad_dtype, S);
-        if (fn) HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsPad));
+        if (fn) HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->s_lds));
     }
     c->stream_momentum = c->tun.stream_via_scratch != 1;
     c->stream_ok = true;
@@ -879,6 +919,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.inv_S = 1.0 / (double)S;
         fa.rho = (float)c->cfg.momentum;
         fa.lambda = (float)c->cfg.weight_decay;
+        fa.win_inv = burst_window_factor(c, S, c->f_grid, std::min(f_lds_tiles, kBurstMax));
         fa.sc = sa;
         void *args[] = {&fa};
         const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
@@ -934,8 +975,11 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.rho = (float)c->cfg.momentum;
         ra.lambda = (float)c->cfg.weight_decay;
         ra.inv_S = 1.0 / (double)S;
+        ra.keep = c->s_keep;
+        ra.win_inv = burst_window_factor(c, S, c->s_grid, c->s_keep);
+        if (ra.win_inv == 0) ra.keep = 0;
         void *args[] = {&ra};
-        HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, kStreamLdsPad, s));
+        HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, c->s_lds, s));
         n_partials = c->s_grid + (ra.n_tiles + 1) / 2;
     }
     // Prior-iteration gain without the streaming kernel: single pass (reduce + update), then the

@@ -203,6 +203,37 @@ def test_poisoned_padding_with_tiles_beyond_the_chip(skew, S, dtype, step_path, 
     H.assert_report(H.run_teacher_forced(wl, skew_elems=skew, poison=True, log=log))
 
 
+# ------------------------------------------------------------------------------ write bursts
+@pytest.mark.parametrize("keep,ticks", [(3, 100), (18, 10 ** 8), (1, 64), (5, 300)],
+                         ids=["short_windows", "ring_fills_first", "one_tile", "five_tiles"])
+@pytest.mark.parametrize("S,dtype", [(3, F32), (16, F32), (8, BF16), (33, BF16)])
+def test_write_bursts_leave_the_same_bits(keep, ticks, S, dtype, step_path, monkeypatch):
+    """Sweeps that write as they read keep finished tiles in LDS and write them in clock windows
+    (by default only from 32 gradient bytes per parameter upwards).  Forced here at every scale,
+    with windows of 1 us (nearly every tile written at once), 3 us, and so long that only a full
+    ring is ever written: parity with the oracle, poisoned padding intact, and w, v bit for bit
+    what the same steps give with every tile written at once."""
+    if step_path == "general":
+        pytest.skip("the general kernels write at once")
+    base = dict(force_path=FORCE_FUSED, fused_max_grid=2) if step_path == "fused" else dict(force_path=FORCE_STREAMING)
+    wl = W.custom([(150001,), (5,), (300000,), (2048,), (77777,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.5,
+                  steps=3, seed=70 + S)
+    monkeypatch.setattr(H, "DEFAULT_TUNING", Tuning(burst_tiles=keep, burst_window_ticks=ticks, **base))
+    H.assert_report(H.run_teacher_forced(wl, skew_elems=1, poison=True, log=log))
+    outs = []
+    for tun in (Tuning(burst_tiles=keep, burst_window_ticks=ticks, **base), Tuning(burst_tiles=-1, **base)):
+        inp = W.Inputs(wl, "cuda:0")
+        gpu = H.make_gpu(wl, tuning=tun)
+        for t in range(3):
+            inp.fill_grads(t)
+            gpu.step(inp.w, inp.v, inp.g)
+        st = gpu.get_state()
+        outs.append((st.tau, st.r, inp.w_flat.clone(), inp.v_flat.clone()))
+        gpu.close()
+    assert outs[0][:2] == outs[1][:2]
+    assert torch.equal(outs[0][2], outs[1][2]) and torch.equal(outs[0][3], outs[1][3])
+
+
 # ---------------------------------------------------------------- pointer sets and failure
 def test_alternating_pointer_sets(step_path):
     """A caller that rotates between three (w, v) pairs and two sets of gradient buffers (six
@@ -470,23 +501,25 @@ def test_error_paths_launch_nothing():
 
 
 def test_default_choice_of_step_path(step_path, monkeypatch):
-    """Left alone, the library takes the fused step while a fair share of the mean gradient fits
-    on chip (cfg3 entirely, cfg4 54 %) and the three-kernel step with the streaming reduce
-    kernel beyond (cfg5: 9 %)."""
+    """Left alone, the library takes the fused step while at least 8 % of the mean gradient fits
+    on chip (cfg3 entirely, cfg4 54 %, cfg5 9 %) and the three-kernel step with the streaming
+    reduce kernel beyond (three times cfg5's list: 3 %)."""
     if step_path != "fused":
         pytest.skip("one run is enough")
     monkeypatch.setattr(H, "DEFAULT_TUNING", None)
     import torch
     from paper_2007_05105_amd import binding
     prop = torch.cuda.get_device_properties(0)
-    for cfg, path in ((1, "fused"), (2, "fused"), (3, "fused"), (4, "fused"), (5, "streaming")):
-        wl = W.config(cfg)
+    for cfg, path in ((1, "fused"), (2, "fused"), (3, "fused"), (4, "fused"), (5, "fused"), (6, "streaming")):
+        wl = W.config(min(cfg, 5))
+        if cfg == 6:        # 1.05 G parameters; a context needs the list, not the tensors
+            wl = W.custom([tuple(s) for s in wl.shapes] * 3, wl.S, grad_dtype=wl.grad_dtype, lr_table=wl.lr_table)
         g = H.make_gpu(wl)
         assert g.step_path() == path and g.uses_fused_step() == (path == "fused"), cfg
         # bytes the kernels move, against a count in Python: on-chip tiles 16 per parameter, tiles whose
         # sweep leaves the momentum in v 20 (24 with weight decay), ragged tiles through the scratch
         full = sum(n // 2048 * 2048 for n in wl.numel)
-        keep = {1: 1.0, 2: 1.0, 3: 1.0, 5: 0.0}.get(cfg)
+        keep = {1: 1.0, 2: 1.0, 3: 1.0, 6: 0.0}.get(cfg)
         if keep is not None:
             per = 16 if keep else (24 if wl.weight_decay else 20)
             ragged = 24 if path == "fused" else 32
@@ -499,7 +532,7 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
         g.close()
     assert (prop.multi_processor_count, prop.shared_memory_per_block) == (256, 160 * 1024)   # what plan() assumes by default
     wl = W.config(5)
-    g = AdaScale(wl.numel, 128, wl.lr_table, grad_dtype=BF16)     # run-time number of half-groups
+    g = AdaScale(wl.numel * 3, 128, wl.lr_table, grad_dtype=BF16)  # run-time number of half-groups
     assert g.step_path() == "streaming"
     g.close()
     g = AdaScale(W.config(3).numel, 128, wl.lr_table, grad_dtype=BF16)
@@ -512,11 +545,17 @@ def test_default_choice_of_step_path(step_path, monkeypatch):
 
 @pytest.mark.parametrize("S,dtype", [(1, F32), (3, F32), (16, F32), (32, F32), (33, F32), (50, F32), (2, BF16), (11, BF16),
                                      (64, BF16), (65, BF16), (128, BF16), (150, BF16)])
-def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, step_path):
+@pytest.mark.parametrize("bursts", [None, (3, 200), (2, 10 ** 8)], ids=["default", "ring_of_3", "ring_of_2_fills_first"])
+def test_streaming_reduce_many_pairs_per_workgroup(S, dtype, bursts, step_path, monkeypatch):
     """Three-kernel step on a list with thousands of tile pairs (each workgroup claims dozens),
-    an odd number of whole tiles, ragged tails and tensors smaller than a tile."""
+    an odd number of whole tiles, ragged tails and tensors smaller than a tile; with the default
+    write bursts (on from 32 gradient bytes per parameter) and with small rings forced at every
+    scale, written in 2 us windows or only when full."""
     if step_path != "three_kernel":
         pytest.skip("three-kernel step only")
+    if bursts:
+        monkeypatch.setattr(H, "DEFAULT_TUNING", Tuning(force_path=FORCE_STREAMING, burst_tiles=bursts[0],
+                                                        burst_window_ticks=bursts[1]))
     wl = W.custom([(2048 * 1501 + 3,), (5,), (2048 * 700,), (2047,), (2048 * 302 + 2047,)], S, grad_dtype=dtype,
                   weight_decay=1e-3, theta=0.5, steps=2, seed=100 + S)
     H.assert_report(H.run_teacher_forced(wl, log=log))
