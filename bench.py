@@ -62,6 +62,7 @@ PROFILE_OF = {
     ("fused", 2): "k_fused_cfg3_resnet50like_S16.md",
     ("fused", 3): "k_fused_cfg3_resnet50like_S16.md",
     ("fused", 4): "k_fused_cfg3_resnet50like_S16.md",
+    ("fused", 5): "k_fused_cfg3_resnet50like_S16.md",
     ("streaming", 3): "three_kernel_step_cfg3_resnet50like_S16.md",
     ("streaming", 5): "three_kernel_streaming_cfg5_transformer350M_S64_bf16.md",
 }

@@ -267,8 +267,8 @@ const void *stream_kernel_for(int dtype, int S)
 #undef KS
 }
 
-// Dynamic LDS the streaming reduce kernel asks for without using it: more than half a CU's LDS,
-// so that its workgroups (one per CU in number) also land one per CU.
+// Least dynamic LDS the streaming reduce kernel asks for (its ring of kept tiles may need less):
+// more than half a CU's LDS, so that its workgroups (one per CU in number) also land one per CU.
 constexpr size_t kStreamLdsPad = 96 * 1024;
 constexpr int kFusedMinPct = 8;   // least share of the mean gradient on chip for the fused step
 
@@ -352,9 +352,10 @@ FusedPlan plan_fused(const adascale_tuning &tun, long long nt, long long nc, int
         f.level = l;
         if (fused_regs_at(l) + f.lds_cap >= f.tpb) break;
     }
-    // with little of the mean gradient on chip the three-kernel step with the streaming reduce
-    // kernel is the faster one (measured crossover: 22-36 % on chip, depending on S and gradient type;
-    // within 3 % of each other from 20 to 37 %)
+    // with very little of the mean gradient on chip the three-kernel step with the streaming reduce
+    // kernel takes over (measured on lists of 62 M to 1.06 G parameters: the fused step is the
+    // faster one by 1-10 % down to 13 % on chip, the two are within 2 % of each other at 9-10 %,
+    // within 3 % either way at 3-5 %, gradients of 32 bytes per parameter and more)
     f.on_chip_pct = f.tpb == 0 ? 100 : std::min(100, 100 * (fused_regs_at(f.level) + std::min(f.tpb, f.lds_cap)) / f.tpb);
     const int min_pct = tun.force_path == ADASCALE_FORCE_FUSED ? 0 : tun.fused_min_percent > 0 ? tun.fused_min_percent : kFusedMinPct;
     if (stream_ok && f.on_chip_pct < min_pct) return f;
