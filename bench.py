@@ -356,7 +356,8 @@ def main() -> int:
             olp.close()
             r = o.pop("roofline")
             if r:
-                o["dominant_kernel"] = {k: r[k] for k in ("kernel", "frac", "frac_moved", "avg_ms", "cold")}
+                o["dominant_kernel"] = {k: r[k] for k in ("kernel", "frac", "frac_moved", "avg_ms", "traffic",
+                                                          "traffic_source", "cold")}
             others.append(o)
 
     out = {
