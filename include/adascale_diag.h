@@ -54,7 +54,7 @@ typedef struct {
     int32_t burst_tiles;         /* sweeps that write as they read (the streaming sweep; the fused step on its
                                     tiles beyond the chip's capacity) keep finished tiles in LDS and write them
                                     in bursts that all workgroups issue in the same clock windows, from 32
-                                    gradient bytes per parameter (S x element size) upwards: < 0 no bursts
+                                    (fused step: 16) gradient bytes per parameter (S x element size) upwards: < 0 no bursts
                                     (every tile written at once), > 0 bursts at any scale, with at most this
                                     many tiles kept by the streaming sweep (up to 18, the default) */
     int32_t burst_window_ticks;  /* > 0: bursts at any scale, in windows of this many ticks of the device's

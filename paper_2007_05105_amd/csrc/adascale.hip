@@ -295,14 +295,16 @@ bool plan_tiles(const long long *numel, int N, long long *full, long long *ragge
 // `grid` workgroups sweep at 6.5 TB/s together, so that the ring is rarely full before a window
 // opens.  Returned as 2^64 / ticks, the factor the kernel turns a clock reading into a window
 // number with; 0 (no bursts) if there is no ring.
-unsigned long long burst_window_factor(const adascale_ctx *c, int S, int grid, int keep)
+unsigned long long burst_window_factor(const adascale_ctx *c, int S, int grid, int keep, double min_grad_bytes)
 {
     if (keep <= 0 || c->tun.burst_tiles < 0) return 0;
     const double b = c->cfg.grad_dtype == ADASCALE_F32 ? 4.0 : 2.0;
     // With few gradient bytes per parameter the writes are too large a share of the sweep to be set
-    // apart: measured at d = 351 M, bursts cost 7-12 % at 2-16 gradient bytes per parameter, gain
-    // 0.7 % at 32, 4-7 % at 64, 6 % at 128.  (A knob that asks for bursts gets them at any scale.)
-    if (S * b < 32.0 && c->tun.burst_tiles == 0 && c->tun.burst_window_ticks <= 0) return 0;
+    // apart.  Measured at d = 351 M: on the streaming sweep bursts cost 7-12 % at 2-16 gradient
+    // bytes per parameter and gain 0.7 % at 32, 4-7 % at 64, 6 % at 128; on the fused step (9 % on
+    // chip) they cost 8 % at 8 bytes and gain 1-7 % at 16, 4-11 % at 24, 11-13 % at 32, 16 % at 128.
+    // (A knob that asks for bursts gets them at any scale.)
+    if (S * b < min_grad_bytes && c->tun.burst_tiles == 0 && c->tun.burst_window_ticks <= 0) return 0;
     double ticks = (double)c->tun.burst_window_ticks;
     if (ticks <= 0) {
         const double tile_bytes = (double)kFTile * (S * b + (c->cfg.weight_decay != 0.0 ? 12.0 : 8.0));
@@ -920,7 +922,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.inv_S = 1.0 / (double)S;
         fa.rho = (float)c->cfg.momentum;
         fa.lambda = (float)c->cfg.weight_decay;
-        fa.win_inv = burst_window_factor(c, S, c->f_grid, std::min(f_lds_tiles, kBurstMax));
+        fa.win_inv = burst_window_factor(c, S, c->f_grid, std::min(f_lds_tiles, kBurstMax), 16.0);
         fa.sc = sa;
         void *args[] = {&fa};
         const size_t lds_bytes = (size_t)f_lds_tiles * kFThreads * sizeof(f4);
@@ -977,7 +979,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         ra.lambda = (float)c->cfg.weight_decay;
         ra.inv_S = 1.0 / (double)S;
         ra.keep = c->s_keep;
-        ra.win_inv = burst_window_factor(c, S, c->s_grid, c->s_keep);
+        ra.win_inv = burst_window_factor(c, S, c->s_grid, c->s_keep, 32.0);
         if (ra.win_inv == 0) ra.keep = 0;
         void *args[] = {&ra};
         HIP_TRY(c, hipLaunchKernel(stream_fn, dim3(c->s_grid), dim3(kFThreads), args, c->s_lds, s));
