@@ -13,14 +13,20 @@ from paper_2007_05105_amd import (BF16, EST_NORM_RATIO, F32, FORCE_FUSED, FORCE_
 
 pytestmark = pytest.mark.gpu
 
-PATHS = {"fused": FORCE_FUSED, "three_kernel": FORCE_STREAMING, "general": FORCE_GENERAL}
+# the three implementations of the step, and the two sweeps that write as they read with their write
+# bursts forced (small rings, 2 us clock windows): the fused step on two workgroups, so that most
+# tiles lie beyond the chip's capacity, and the streaming sweep
+PATHS = {"fused": dict(force_path=FORCE_FUSED), "three_kernel": dict(force_path=FORCE_STREAMING),
+         "general": dict(force_path=FORCE_GENERAL),
+         "fused_beyond_capacity_bursts": dict(force_path=FORCE_FUSED, fused_max_grid=2, burst_tiles=3, burst_window_ticks=200),
+         "three_kernel_bursts": dict(force_path=FORCE_STREAMING, burst_tiles=3, burst_window_ticks=200)}
 
 
 @pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("S,dtype,flags", [(8, F32, 0), (8, F32, LAGGED_R), (5, BF16, EST_NORM_RATIO)])
 def test_captured_step_replays_like_direct_steps(path, S, dtype, flags):
     T = 7
-    tun = Tuning(force_path=PATHS[path])
+    tun = Tuning(**PATHS[path])
     wl = W.custom([(300000,), (999,), (70001,), (2048 * 40,)], S, grad_dtype=dtype, weight_decay=1e-3, theta=0.7,
                   lr_table=W.lr_step_decay(0.1, 40), steps=T, seed=91)
 
