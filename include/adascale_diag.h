@@ -70,7 +70,8 @@ int adascale_init_tuned(const adascale_config *cfg, const adascale_tuning *tunin
  * one arrival more than its grid provides, so every workgroup's bounded wait runs out (set
  * barrier_spin_limit small to keep that short), every kernel exits normally, and the context ends
  * up in the failed state adascale_get_state describes.  ESTATE if the context does not take the
- * fused step with a barrier (see adascale_step_path; ADASCALE_LAGGED_R has no barrier).
+ * fused step with a barrier (see adascale_step_path; with ADASCALE_LAGGED_R small parameter lists
+ * run instances of the fused step that have none).
  */
 int adascale_fail_next_barrier(adascale_ctx *ctx);
 

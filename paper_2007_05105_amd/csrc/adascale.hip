@@ -442,12 +442,15 @@ int setup_fused(adascale_ctx *c)
     const size_t lds_bytes = (size_t)f.lds_cap * kFThreads * sizeof(f4);
     const int max_scale = (c->cfg.grad_dtype == ADASCALE_F32 ? kFMaxScaleF32 : kFMaxScaleBf16) + 1;  // + the run-time shape
     for (int S = 1; S <= max_scale; ++S) {
-        const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, f.level, (c->cfg.flags & ADASCALE_LAGGED_R) != 0);
-        if (!fn) continue;
-        HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
-        int per_cu = 0;
-        HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
-        if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < f.grid) return ADASCALE_OK;
+        // with ADASCALE_LAGGED_R either variant may run, depending on the scale of the moment
+        for (int lag = 0; lag <= ((c->cfg.flags & ADASCALE_LAGGED_R) ? 1 : 0); ++lag) {
+            const void *fn = fused_kernel_for(c->cfg.grad_dtype, S, f.level, lag != 0);
+            if (!fn) continue;
+            HIP_TRY(c, hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes));
+            int per_cu = 0;
+            HIP_TRY(c, hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kFThreads, lds_bytes));
+            if (per_cu < 1 || (long long)per_cu * prop.multiProcessorCount < f.grid) return ADASCALE_OK;
+        }
     }
     c->f_grid = f.grid;
     c->f_tpb = f.tpb;
@@ -493,6 +496,22 @@ void launch_reduce_update(const adascale_ctx *c, const unsigned long long *d_ptr
 }
 
 
+// ADASCALE_LAGGED_R on the fused step.  eta_t is known before any gradient is read, so the grid
+// barrier is not needed for the result, and the instances without it (k_scalars behind them)
+// save its 2.5 us: 15.3 against 17.7 us at d = 1 M, S = 4.  But the barrier also keeps phase 2's
+// writes of the early workgroups out of the late workgroups' gradient sweep, and on anything
+// larger that is worth more: with the barrier 87.6 against 92.6 us at d = 11 M, S = 8, 312.7
+// against 317-324 us at d = 25.6 M, S = 16, 7.58 against 7.71 ms at d = 351 M, S = 64 bf16 (one
+// session; the barrier kernel evaluates the same prior-iteration gain itself).  The instances
+// without barrier are taken while a workgroup's share of the step is estimated below 50 us.
+bool lag_barrier_free(const adascale_ctx *c, int S)
+{
+    if (!(c->cfg.flags & ADASCALE_LAGGED_R)) return false;
+    const double b = c->cfg.grad_dtype == ADASCALE_F32 ? 4.0 : 2.0;
+    const double us = (double)c->f_tpb * kFTile * (S * b + 16.0) / 27.0e3;  // 27 GB/s per workgroup at 6.9 TB/s
+    return us < 50.0;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -510,8 +529,8 @@ int64_t adascale_step_bytes(const adascale_ctx *c)
 int adascale_step_path(const adascale_ctx *c)
 {
     if (!c) return ADASCALE_PATH_GENERAL;
-    const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
-    if (c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag)) return ADASCALE_PATH_FUSED;
+    if (c->fused_ok && fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag_barrier_free(c, c->cfg.S)))
+        return ADASCALE_PATH_FUSED;
     if (c->stream_ok && stream_kernel_for(c->cfg.grad_dtype, c->cfg.S)) return ADASCALE_PATH_STREAMING;
     return ADASCALE_PATH_GENERAL;
 }
@@ -570,7 +589,7 @@ int adascale_uses_fused_step(const adascale_ctx *c) { return adascale_step_path(
 int adascale_fail_next_barrier(adascale_ctx *c)
 {
     if (!c) return ADASCALE_EINVAL;
-    if (adascale_step_path(c) != ADASCALE_PATH_FUSED || (c->cfg.flags & ADASCALE_LAGGED_R))
+    if (adascale_step_path(c) != ADASCALE_PATH_FUSED || lag_barrier_free(c, c->cfg.S))
         return fail(c, ADASCALE_ESTATE, "the next step has no grid barrier");
     c->fail_next = true;
     return ADASCALE_OK;
@@ -595,7 +614,7 @@ int64_t adascale_step_moved_bytes(const adascale_ctx *c)
     }
     // fused: workgroup b holds full tiles b, b + G, ...; the first q_hbm of them stay on chip
     int regs = 0;
-    (void)fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag, &regs);
+    (void)fused_kernel_for(c->cfg.grad_dtype, c->cfg.S, c->f_level, lag_barrier_free(c, c->cfg.S), &regs);
     const int q_hbm = std::min(regs + std::max(0, std::min(c->f_tpb - regs, c->f_lds_cap)), c->f_tpb);
     const int64_t nt = (int64_t)c->ftiles.size();
     int64_t on_chip = 0;
@@ -897,7 +916,8 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
     ScalarArgs sa{S, c->cfg.flags, c->cfg.theta, c->cfg.eps, (long long)c->cfg.lr_table_len};
     const bool lag = (c->cfg.flags & ADASCALE_LAGGED_R) != 0;
     int f_regs = 0;
-    const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag, &f_regs) : nullptr;
+    const bool lag_kernel = lag_barrier_free(c, S);
+    const void *fused_fn = c->fused_ok ? fused_kernel_for(c->cfg.grad_dtype, S, c->f_level, lag_kernel, &f_regs) : nullptr;
     const int f_lds_tiles = std::max(0, std::min(c->f_tpb - f_regs, c->f_lds_cap));
     if (fused_fn) {
         FusedArgs fa{};
@@ -909,7 +929,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
         fa.partials = c->d_partials;
         fa.book = c->d_book;
         fa.lr = c->d_lr;
-        fa.barrier_extra = c->fail_next && !lag ? 1 : 0;  // adascale_fail_next_barrier: an arrival that never comes
+        fa.barrier_extra = c->fail_next && !lag_kernel ? 1 : 0;  // adascale_fail_next_barrier: an arrival that never comes
         c->fail_next = false;
         fa.spin_limit = c->tun.barrier_spin_limit > 0 ? c->tun.barrier_spin_limit : kFSpinLimit;
         fa.n_tiles = (int)c->ftiles.size();
@@ -948,7 +968,7 @@ int adascale_step(adascale_ctx *c, void *const *w, void *const *mom, const void 
             ch.last_stream = s;
         }
         if (pe) HIP_TRY(c, hipEventRecord(pe[1], s));
-        if (lag) {
+        if (lag_kernel) {
             hipLaunchKernelGGL(k_scalars, dim3(1), dim3(kScalarThreads), 0, s, c->d_partials, c->f_grid, c->d_book, c->d_lr,
                                sa);
             HIP_TRY(c, hipGetLastError());

@@ -137,8 +137,9 @@ def test_variants_of_the_estimator(flags):
 
 @pytest.mark.parametrize("S,dtype", [(16, F32), (4, F32), (32, BF16), (5, F32), (64, BF16), (29, F32), (40, F32)])
 def test_lagged_gain_single_pass_medium(S, dtype, step_path):
-    """Prior-iteration gain on shapes that span many tiles per workgroup (fused step without its
-    grid barrier; streaming reduce, scalars, update; beyond their scales one sweep that reduces
+    """Prior-iteration gain on shapes that span many tiles per workgroup (fused step: without its
+    grid barrier at S = 4, 5, where a workgroup's share of the step is short, with it at the
+    larger scales; streaming reduce, scalars, update; beyond their scales one sweep that reduces
     and updates, then the scalars)."""
     wl = W.custom([(3_000_000,), (70001,), (513,), (1_200_000,)], S, grad_dtype=dtype, weight_decay=1e-4, theta=0.9,
                   lr_table=W.lr_step_decay(0.1, 64), steps=3, seed=41)
