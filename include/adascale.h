@@ -48,9 +48,10 @@ enum { ADASCALE_F32 = 0, ADASCALE_BF16 = 1 }; /* gradient element type */
 /* adascale_config.flags */
 enum {
     /* r_t from the averages of PRIOR iterations only, r_0 = 1 (the variant App. B.3 says
-     * its experiments used); eta_t is then known before the gradients are read, so the fused
-     * step needs no grid barrier and the general step is a single sweep.  Default (flag
-     * clear): current-iteration estimate, which App. B.3 recommends. */
+     * its experiments used); eta_t is then known before the gradients are read, so the general
+     * step is a single sweep and the fused step runs without its grid barrier where that is the
+     * faster form (small parameter lists).  Default (flag clear): current-iteration estimate,
+     * which App. B.3 recommends. */
     ADASCALE_LAGGED_R = 1u,
     /* Estimator of Sec. 3.4: moving averages m1 of A/S and m2 of B,
      * r_t = (m1 + eps) / (m2 + eps), instead of the (s2, m2) estimator of App. B.3. */
